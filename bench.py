@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the StructKV scoring / selection / gather sweep on one MI355X.
+
+A step = one pass of the whole hot path over every layer of one synthetic prefill:
+for each layer  score_layer -> accumulate_centrality -> select_topk(D, k, keep window) -> gather_kv,
+then one select_topk on the accumulated centrality.  Inputs (per-layer Q_win, K, V) are generated
+on the GPU before the timed region and stay resident in HBM; each layer has its own buffers.
+
+Prints ONE JSON line: scored KV tokens/s for the whole sweep, the HBM roofline of the dominant kernel
+(timed live with events in a separate profiled sweep of the same sequence), and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3_llama8b_128k")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
+                    help="graph: the sweep is captured once in a HIP graph and replayed per step")
+    ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
+    ap.add_argument("--cpu-sample-layers", type=int, default=8, help="layers the CPU oracle is timed on (0 = skip)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+                         "(the sharding design is described in DESIGN.md).\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_2604_06746_amd import binding as B
+    from paper_2604_06746_amd import sweep as sweep_mod
+
+    wl = workloads.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    L = wl.n_layers
+    layers = [workloads.make_layer(wl, l, "cuda") for l in range(L)]
+    torch.cuda.synchronize()
+    sw = sweep_mod.LayerSweep(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.torch_dtype,
+                              wl.seq_lens, wl.k_per_seq, lam=wl.lam, n_layers_out=L)
+
+    def step():
+        sw.reset()
+        for l in range(L):
+            x = layers[l]
+            sw.layer(x.q_win, x.k, x.v, slot=l)
+        sw.select_struct()
+
+    mode = args.mode
+    graph = None
+    if mode == "graph":
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()                      # warm every kernel outside capture
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            run = graph.replay
+        except Exception as e:  # capture unavailable: time eager launches instead
+            sys.stderr.write("bench.py: graph capture failed (%s); timing eager launches\n" % e)
+            mode, graph, run = "eager", None, step
+    else:
+        run = step
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_step = wl.total_tokens * L
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations: the same sequence, eager, with an event between every kernel ----
+    names = ["score_pass1", "score_combine", "score_pass2", "score_reduce", "accumulate", "select_topk", "gather_kv"]
+    acc_ms = {k: 0.0 for k in names}
+    n_meas = 0
+    stream = torch.cuda.current_stream()
+    for _ in range(max(args.profile_steps, 0)):
+        sw.reset()
+        torch.cuda.synchronize()
+        torch.cuda._sleep(int(60e6))          # let the host run ahead so no launch gap lands inside a bracket
+        evs = []
+        for l in range(L):
+            x = layers[l]
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+            e[0].record(stream)
+            for i, mask in enumerate((1, 2, 4, 8)):
+                B.structkv_debug_score_steps(sw.shape, x.q_win, x.k, sw.cu, sw.indeg, sw.entropy,
+                                             sw.entropy_per_head, sw.workspace, mask)
+                e[i + 1].record(stream)
+            sw.accumulate(); e[5].record(stream)
+            sw.select_kv(); e[6].record(stream)
+            sw.gather(x.k, x.v, l); e[7].record(stream)
+            evs.append(e)
+        torch.cuda.synchronize()
+        for e in evs:
+            for i, k in enumerate(names):
+                acc_ms[k] += e[i].elapsed_time(e[i + 1])
+        n_meas += L
+    kern_us = {k: (1e3 * v / n_meas if n_meas else None) for k, v in acc_ms.items()}
+
+    k_bytes = wl.n_kv_heads * wl.head_dim * wl.elem_bytes * wl.total_tokens       # K read once, per launch
+    rows = sum(k + wl.window for k in wl.k_per_seq)
+    gather_bytes = 2 * 2 * rows * wl.n_kv_heads * wl.head_dim * wl.elem_bytes + 4 * rows
+    roofline = None
+    extra = {}
+    if n_meas:
+        dom = "score_pass1" if kern_us["score_pass1"] >= kern_us["score_pass2"] else "score_pass2"
+        achieved = k_bytes / (kern_us[dom] * 1e-6) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                traffic = json.load(open(tpath)).get(wl.name, {}).get(dom)
+            except Exception:
+                traffic = None
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": round(kern_us[dom], 2)}
+        score_us = sum(kern_us[k] for k in names[:4])
+        extra = {
+            "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
+            "k_stream_both_passes": {"achieved_GBs": round(k_bytes / (score_us * 1e-6) / 1e9, 1),
+                                     "frac": round(k_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+            "gather": {"achieved_GBs": round(gather_bytes / (kern_us["gather_kv"] * 1e-6) / 1e9, 1),
+                       "frac": round(gather_bytes / (kern_us["gather_kv"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                       "algorithmic_bytes_per_launch": gather_bytes},
+        }
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if args.cpu_sample_layers > 0:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from helpers import to_oracle_array
+        ns = min(args.cpu_sample_layers, L)
+        sample = sorted(set(int(round(i * (L - 1) / max(ns - 1, 1))) for i in range(ns)))
+        C = np.zeros(wl.total_tokens)
+        cpu_s = 0.0
+        for l in sample:
+            x = layers[l]
+            qh, kh, vh = to_oracle_array(x.q_win), to_oracle_array(x.k), to_oracle_array(x.v)
+            c0 = time.perf_counter()
+            D, ent, _, _ = oracle.score_layer(qh, kh, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window,
+                                              wl.seq_lens)
+            oracle.accumulate(C, D, wl.lam, 1.0 / wl.window)
+            idx = oracle.select_topk(D, wl.seq_lens, wl.k_per_seq, wl.window)
+            oracle.gather_kv(kh, idx, wl.seq_lens)
+            oracle.gather_kv(vh, idx, wl.seq_lens)
+            cpu_s += time.perf_counter() - c0
+        cpu = {"value": round(wl.total_tokens * len(sample) / cpu_s, 1), "unit": "scored KV tokens/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%d of %d layers (%s) of %s, all tokens; %.1f s" % (len(sample), L, sample, wl.name, cpu_s)}
+
+    out = {
+        "metric": "scored KV tokens/s per layer sweep (score+top-k+gather)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
+                   "head_dim": wl.head_dim, "seq_lens": list(wl.seq_lens) if wl.batch > 1 else wl.seq_lens[0],
+                   "window": wl.window, "k": list(wl.k_per_seq) if wl.batch > 1 else wl.k_per_seq[0],
+                   "launch": mode},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,160 @@
+/*
+ * libstructkv -- StructKV prefill scoring / selection / gather path for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every tensor pointer is a DEVICE pointer unless marked "host".  The
+ * library owns no memory and keeps no state between calls (the debug path
+ * switch aside): the caller owns all
+ * buffers, including the scratch `workspace` (size it with
+ * structkv_workspace_bytes).  All work is enqueued on `stream` (a hipStream_t
+ * passed as void*; NULL = the default stream); no call synchronises the
+ * device.  Every entry point returns a structkv_status; on failure nothing has
+ * been enqueued unless the status is STRUCTKV_ERR_HIP, and
+ * structkv_last_error() holds a thread-local message.  Inputs are assumed
+ * finite (NaN/Inf behaviour is undefined).  Strides count ELEMENTS and are
+ * 64-bit.  Outputs are overwritten in full except `centrality` (in/out).
+ *
+ * Notation (StructKV paper, Sec. 3.2): H_q query heads, G KV heads (GQA group
+ * size H_q/G), d head dim, n cached tokens of a sequence, w observation
+ * window (the last w positions n-w .. n-1), k selection budget, lambda decay.
+ * A call handles a ragged batch of B sequences packed along the token axis:
+ * sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.
+ */
+#ifndef STRUCTKV_H
+#define STRUCTKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  STRUCTKV_OK = 0,
+  STRUCTKV_ERR_INVALID_ARG = 1, /* NULL pointer, bad size, inconsistent cu_seqlens, k out of range */
+  STRUCTKV_ERR_UNSUPPORTED = 2, /* dtype / head_dim / batch beyond what the kernels implement */
+  STRUCTKV_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or smaller than required */
+  STRUCTKV_ERR_HIP = 4          /* a HIP runtime call failed (message has hipGetErrorString) */
+} structkv_status;
+
+enum { STRUCTKV_DTYPE_F32 = 0, STRUCTKV_DTYPE_BF16 = 1 };
+
+/* Largest batch one call accepts. */
+#define STRUCTKV_MAX_BATCH 64
+
+typedef struct {
+  int32_t n_q_heads;  /* H_q >= 1 */
+  int32_t n_kv_heads; /* G >= 1, divides H_q */
+  int32_t head_dim;   /* d: 1..256; the bf16 MFMA path needs d in {64,128}, other shapes take a SIMT path */
+  int32_t window;     /* w >= 1 */
+  int32_t dtype;      /* STRUCTKV_DTYPE_F32 or STRUCTKV_DTYPE_BF16: element type of q_win and k */
+  int32_t causal;     /* 0 (Eq. 1 as written): each window query sees all n keys;
+                         1: window row i (position n-w+i) sees keys j <= n-w+i only (needs n >= w) */
+  float scale;        /* logit scale, >= 0; 0 selects 1/sqrt(head_dim) (Eq. 1) */
+} structkv_shape;
+
+/* Thread-local message of the last failing call on this thread ("" if none). */
+const char* structkv_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t structkv_version(void);
+
+/*
+ * Bytes of scratch that structkv_score_layer (shape != NULL) and structkv_select_topk need
+ * for a batch of `batch` sequences holding `total_tokens` tokens in all.  With shape == NULL
+ * only the top-k requirement is returned.  Returns 0 on invalid arguments.  The workspace must
+ * be 256-byte aligned; its contents need not be preserved between calls and need no initialisation.
+ */
+size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens);
+
+/*
+ * Per-layer scoring pass (paper Eq. 1, Eq. 2 without its 1/w, Eq. 4).
+ * For every sequence b, every query head h (KV head g = h / (H_q/G)) and every window row i:
+ *   a_{h,i,j} = softmax_j( scale * q_win[b][h][i] . k[g][cu[b]+j] ),  j in [0, n_b)
+ *   indeg_out[cu[b]+j]  = sum_{h,i} a_{h,i,j}            (raw in-degree D_j; sums to w*H_q per sequence)
+ *   entropy_out[b]      = -(1/(H_q w)) sum_{h,i,j} a ln a (natural log, 0 ln 0 = 0)
+ *   entropy_per_head_out[b][h] = -(1/w) sum_{i,j} a ln a  (optional, may be NULL)
+ * q_win : [B][H_q][w][d] contiguous, dtype per shape.
+ * k     : element (g, token t, c) at k[g*k_stride_head + t*k_stride_tok + c], c contiguous, t packed over the batch.
+ * cu_seqlens : HOST pointer, [B+1], cu[0]=0, non-decreasing, cu[B] = total tokens; n_b = 0 is allowed
+ *              (no output, entropy 0), otherwise n_b >= 1 (and n_b >= w if causal).
+ * indeg_out [total], entropy_out [B], entropy_per_head_out [B][H_q]: fp32.
+ * Deterministic: the same inputs give bit-identical outputs (no floating-point atomics).
+ */
+structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
+                                     int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                     const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
+                                     float* entropy_per_head_out, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+/*
+ * Global in-degree centrality update (paper Eq. 3 as the recurrence of Alg. 1 line 6, with
+ * Eq. 2's 1/w applied here):  centrality[t] = lambda*centrality[t] + inv_w*indeg[t], t < total_tokens.
+ * lambda in (0,1]; inv_w > 0 (normally 1/w).  centrality is in/out, fp32; start it at zero.
+ */
+structkv_status structkv_accumulate_centrality(float* centrality, const float* indeg,
+                                               int64_t total_tokens, float lambda, float inv_w,
+                                               void* stream);
+
+/*
+ * Token selection (paper Eq. 10 on the centrality, Eq. 13 on a layer's scores): per sequence b the
+ * k_b largest of scores[cu[b] .. cu[b+1]-keep_tail) -- ties go to the lower index -- united with the
+ * last keep_tail positions (the observation window I_win).  Written in ascending order as
+ * sequence-local int32 indices at idx_out + sum_{b'<b}(k_b' + keep_tail);  k_b + keep_tail entries.
+ * scores : [total] fp32.  cu_seqlens, k_per_seq : HOST pointers ([B+1], [B]).
+ * Requires 0 <= keep_tail <= n_b and 0 <= k_b <= n_b - keep_tail for every b; n_b < 2^31.
+ * Deterministic and exact: the result is the unique set defined above for the given fp32 scores
+ * (-0.0 and +0.0 compare equal).
+ */
+structkv_status structkv_select_topk(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                     const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Decoupled cache store (paper Alg. 1 line 17): compact the selected K and V rows.
+ *   dst[g][o_b + i][:] = src[g][cu[b] + idx[o_b + i]][:],  o_b = sum_{b'<b} rows_b',  i < rows_b
+ * for K and V (either pair may be NULL to skip it), bit-exact copy of head_dim*elem_bytes bytes per row.
+ * idx : DEVICE pointer, sequence-local int32 indices laid out as structkv_select_topk writes them;
+ *       every index must lie in [0, n_b) (checked on the device: an out-of-range index copies row 0
+ *       of the sequence instead of faulting).
+ * rows_per_seq : HOST pointer [B] (k_b + keep_tail).  elem_bytes in {2,4}.
+ */
+structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t src_stride_head,
+                                   int64_t src_stride_tok, void* k_dst, void* v_dst,
+                                   int64_t dst_stride_head, int64_t dst_stride_tok, int32_t n_kv_heads,
+                                   int32_t head_dim, int32_t elem_bytes, int32_t batch,
+                                   const int64_t* cu_seqlens, const int64_t* rows_per_seq,
+                                   const int32_t* idx, void* stream);
+
+/*
+ * Test hook: the attention rows themselves (paper Eq. 1) for ONE sequence of n tokens,
+ * probs_out [H_q][w][n] fp32, computed by the same kernels as structkv_score_layer.
+ * H_q*w*n must not exceed 2^26.
+ */
+structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_win, const void* k,
+                                     int64_t k_stride_head, int64_t k_stride_tok, int64_t n,
+                                     float* probs_out, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
+/*
+ * Profiling hook: structkv_score_layer with only some of its four kernels enqueued, so a caller can
+ * bracket each with events.  step_mask bits: 1 = pass 1 (row statistics), 2 = combine (lse, entropy
+ * per head), 4 = pass 2 (column sums), 8 = reduce (in-degree, entropy).  Steps read what earlier steps
+ * left in the workspace; mask 15 is structkv_score_layer itself.
+ */
+structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,
+                                           int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                           const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
+                                           float* entropy_per_head_out, void* workspace,
+                                           size_t workspace_bytes, void* stream, int32_t step_mask);
+
+/*
+ * Test hook: force the scoring path.  0 = automatic (bf16 MFMA kernels when the shape and alignment
+ * allow, SIMT kernels otherwise), 1 = always SIMT.  Process-wide; returns the previous value.
+ */
+int32_t structkv_debug_force_path(int32_t path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRUCTKV_H */

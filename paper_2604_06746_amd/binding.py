@@ -1,0 +1,175 @@
+"""ctypes binding of libstructkv.so: same names as the C entry points, marshalling only.
+
+Tensors are torch tensors (device memory + streams are PyTorch's job); every step of the path
+runs inside the library's HIP kernels.  cu_seqlens / k_per_seq / rows_per_seq are host sequences.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstructkv.so")
+
+STRUCTKV_OK = 0
+STRUCTKV_ERR_INVALID_ARG = 1
+STRUCTKV_ERR_UNSUPPORTED = 2
+STRUCTKV_ERR_WORKSPACE = 3
+STRUCTKV_ERR_HIP = 4
+STRUCTKV_DTYPE_F32 = 0
+STRUCTKV_DTYPE_BF16 = 1
+STRUCTKV_MAX_BATCH = 64
+
+EXPORTS = (
+    "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
+    "structkv_accumulate_centrality", "structkv_select_topk", "structkv_gather_kv",
+    "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
+)
+
+
+class structkv_shape(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("window", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class StructKVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("structkv status %d: %s" % (status, message))
+        self.status = status
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libstructkv.so is not built: run `python -m paper_2604_06746_amd.build` "
+                      "(hipcc, --offload-arch=gfx950).  There is no fallback path.")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+_sp = ctypes.POINTER(structkv_shape)
+_lib.structkv_last_error.restype = ctypes.c_char_p
+_lib.structkv_last_error.argtypes = []
+_lib.structkv_version.restype = _i32
+_lib.structkv_workspace_bytes.restype = _sz
+_lib.structkv_workspace_bytes.argtypes = [_sp, _i32, _i64]
+_lib.structkv_score_layer.restype = _i32
+_lib.structkv_score_layer.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.structkv_debug_score_steps.restype = _i32
+_lib.structkv_debug_score_steps.argtypes = _lib.structkv_score_layer.argtypes + [_i32]
+_lib.structkv_accumulate_centrality.restype = _i32
+_lib.structkv_accumulate_centrality.argtypes = [_vp, _vp, _i64, _f32, _f32, _vp]
+_lib.structkv_select_topk.restype = _i32
+_lib.structkv_select_topk.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+_lib.structkv_gather_kv.restype = _i32
+_lib.structkv_gather_kv.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp,
+                                    _vp, _vp, _vp]
+_lib.structkv_debug_probs.restype = _i32
+_lib.structkv_debug_probs.argtypes = [_sp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
+_lib.structkv_debug_force_path.restype = _i32
+_lib.structkv_debug_force_path.argtypes = [_i32]
+
+
+def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, window: int, dtype: int,
+               causal: bool = False, scale: float = 0.0) -> structkv_shape:
+    return structkv_shape(n_q_heads, n_kv_heads, head_dim, window, dtype, int(bool(causal)), float(scale))
+
+
+def _host_i64(values: Sequence[int]):
+    return (ctypes.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status: int) -> None:
+    if status != STRUCTKV_OK:
+        raise StructKVError(status, _lib.structkv_last_error().decode())
+
+
+def structkv_last_error() -> str:
+    return _lib.structkv_last_error().decode()
+
+
+def structkv_version() -> int:
+    return int(_lib.structkv_version())
+
+
+def structkv_debug_force_path(path: int) -> int:
+    return int(_lib.structkv_debug_force_path(path))
+
+
+def structkv_workspace_bytes(shape: Optional[structkv_shape], batch: int, total_tokens: int) -> int:
+    return int(_lib.structkv_workspace_bytes(ctypes.byref(shape) if shape is not None else None, batch,
+                                             total_tokens))
+
+
+def structkv_score_layer(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
+                         cu_seqlens: Sequence[int], indeg_out: torch.Tensor, entropy_out: torch.Tensor,
+                         entropy_per_head_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                         stream=None) -> None:
+    """k: [G, total, d] view with d contiguous (head/token strides are passed through)."""
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous()
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_score_layer(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                     len(cu_seqlens) - 1, cu, _ptr(indeg_out), _ptr(entropy_out),
+                                     _ptr(entropy_per_head_out), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def structkv_debug_score_steps(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
+                               cu_seqlens: Sequence[int], indeg_out: torch.Tensor, entropy_out: torch.Tensor,
+                               entropy_per_head_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                               step_mask: int, stream=None) -> None:
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_debug_score_steps(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                           len(cu_seqlens) - 1, cu, _ptr(indeg_out), _ptr(entropy_out),
+                                           _ptr(entropy_per_head_out), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream(stream),
+                                           step_mask))
+
+
+def structkv_accumulate_centrality(centrality: torch.Tensor, indeg: torch.Tensor, lam: float, inv_w: float,
+                                   stream=None) -> None:
+    assert centrality.numel() == indeg.numel()
+    _check(_lib.structkv_accumulate_centrality(_ptr(centrality), _ptr(indeg), centrality.numel(), lam, inv_w,
+                                               _stream(stream)))
+
+
+def structkv_select_topk(scores: torch.Tensor, cu_seqlens: Sequence[int], k_per_seq: Sequence[int],
+                         keep_tail: int, idx_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    cu, ks = _host_i64(cu_seqlens), _host_i64(k_per_seq)
+    _check(_lib.structkv_select_topk(_ptr(scores), len(k_per_seq), cu, ks, keep_tail, _ptr(idx_out),
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)))
+
+
+def structkv_gather_kv(k_src: Optional[torch.Tensor], v_src: Optional[torch.Tensor],
+                       k_dst: Optional[torch.Tensor], v_dst: Optional[torch.Tensor],
+                       cu_seqlens: Sequence[int], rows_per_seq: Sequence[int], idx: torch.Tensor,
+                       stream=None) -> None:
+    """src/dst: [G, tokens, d] views with d contiguous; K and V must share strides."""
+    src = k_src if k_src is not None else v_src
+    dst = k_dst if k_dst is not None else v_dst
+    if v_src is not None and k_src is not None:
+        assert v_src.stride() == k_src.stride() and v_dst.stride() == k_dst.stride()
+    cu, rows = _host_i64(cu_seqlens), _host_i64(rows_per_seq)
+    _check(_lib.structkv_gather_kv(_ptr(k_src), _ptr(v_src), src.stride(0), src.stride(1), _ptr(k_dst),
+                                   _ptr(v_dst), dst.stride(0), dst.stride(1), src.shape[0], src.shape[2],
+                                   src.element_size(), len(rows_per_seq), cu, rows, _ptr(idx),
+                                   _stream(stream)))
+
+
+def structkv_debug_probs(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, n: int,
+                         probs_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(_lib.structkv_debug_probs(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1), n,
+                                     _ptr(probs_out), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))

@@ -1,0 +1,342 @@
+// C-ABI entry points of libstructkv: argument validation, work planning, workspace carving and
+// kernel launches.  No device memory is allocated here; nothing synchronises the device.
+#include "common.h"
+
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace skv {
+
+static thread_local char g_err[512] = "";
+static std::atomic<int> g_force_path{0};
+
+structkv_status fail(structkv_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+void clear_error() { g_err[0] = 0; }
+
+namespace {
+
+structkv_status check_shape(const structkv_shape* s) {
+  if (!s) return fail(STRUCTKV_ERR_INVALID_ARG, "shape is NULL");
+  if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads)
+    return fail(STRUCTKV_ERR_INVALID_ARG, "n_kv_heads (%d) must be >= 1 and divide n_q_heads (%d)",
+                s->n_kv_heads, s->n_q_heads);
+  if (s->window < 1) return fail(STRUCTKV_ERR_INVALID_ARG, "window must be >= 1, got %d", s->window);
+  if (s->head_dim < 1) return fail(STRUCTKV_ERR_INVALID_ARG, "head_dim must be >= 1, got %d", s->head_dim);
+  if (s->head_dim > 256) return fail(STRUCTKV_ERR_UNSUPPORTED, "head_dim %d > 256", s->head_dim);
+  if (s->dtype != STRUCTKV_DTYPE_F32 && s->dtype != STRUCTKV_DTYPE_BF16)
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "dtype %d is neither f32 (0) nor bf16 (1)", s->dtype);
+  if (s->causal != 0 && s->causal != 1) return fail(STRUCTKV_ERR_INVALID_ARG, "causal must be 0 or 1");
+  if (!(s->scale >= 0.f) || !std::isfinite(s->scale))
+    return fail(STRUCTKV_ERR_INVALID_ARG, "scale must be finite and >= 0 (0 = 1/sqrt(head_dim))");
+  if ((int64_t)(s->n_q_heads / s->n_kv_heads) * s->window > 65536)
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "more than 65536 query rows per KV head");
+  return STRUCTKV_OK;
+}
+
+structkv_status check_cu(int32_t batch, const int64_t* cu, SeqTable* seq) {
+  if (batch < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "batch must be >= 0, got %d", batch);
+  if (batch > kMaxBatch)
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "batch %d exceeds STRUCTKV_MAX_BATCH (%d)", batch, kMaxBatch);
+  if (!cu) return fail(STRUCTKV_ERR_INVALID_ARG, "cu_seqlens is NULL");
+  if (cu[0] != 0) return fail(STRUCTKV_ERR_INVALID_ARG, "cu_seqlens[0] must be 0");
+  memset(seq, 0, sizeof(*seq));
+  seq->batch = batch;
+  for (int b = 0; b < batch; ++b) {
+    if (cu[b + 1] < cu[b]) return fail(STRUCTKV_ERR_INVALID_ARG, "cu_seqlens decreases at %d", b);
+    if (cu[b + 1] - cu[b] >= ((int64_t)1 << 31))
+      return fail(STRUCTKV_ERR_UNSUPPORTED, "sequence %d has 2^31 or more tokens", b);
+  }
+  for (int b = 0; b <= batch; ++b) seq->cu[b] = cu[b];
+  return STRUCTKV_OK;
+}
+
+// Decide path, tiling and workspace layout.  `n_chunk_bound` < 0: exact from seq; otherwise an upper bound.
+void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t total, bool mfma_ok,
+               ScorePlan* p) {
+  const int gs = s.n_q_heads / s.n_kv_heads;
+  p->R = gs * s.window;
+  p->path = mfma_ok ? 0 : 1;
+  if (p->path == 0) {
+    if (p->R > 128) { p->RPC = 256; p->RB = 2; p->WR = 4; p->WK = 1; }
+    else if (p->R > 64) { p->RPC = 128; p->RB = 1; p->WR = 4; p->WK = 1; }
+    else { p->RPC = 64; p->RB = 1; p->WR = 2; p->WK = 2; }
+    p->RC = (int)ceil_div(p->R, p->RPC);
+    // keys per workgroup: long chunks amortise the query-operand load; keep >= ~1024 workgroups
+    int kc = 1024;
+    while (kc > 256 && ceil_div(total, kc) * s.n_kv_heads * p->RC < 1024) kc >>= 1;
+    p->KC = kc;
+  } else {
+    p->RPC = 16; p->RB = 0; p->WR = 0; p->WK = 1;
+    p->RC = (int)ceil_div(p->R, p->RPC);
+    p->KC = 256;
+  }
+  if (seq) {
+    p->n_chunks = 0;
+    for (int b = 0; b < batch; ++b) p->n_chunks += ceil_div(seq->cu[b + 1] - seq->cu[b], p->KC);
+  } else {
+    p->n_chunks = total / p->KC + batch;
+  }
+  const size_t GRC = (size_t)s.n_kv_heads * p->RC;
+  size_t off = 0;
+  p->off_stats = off;   off += align_up(sizeof(float) * GRC * (size_t)p->n_chunks * p->WK * 3 * p->RPC, 256);
+  p->off_lse = off;     off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads * s.window, 256);
+  p->off_colsum = off;  off += align_up(sizeof(float) * GRC * (size_t)total, 256);
+  p->off_enthead = off; off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads, 256);
+  p->total_bytes = off;
+}
+
+bool mfma_eligible(const structkv_shape& s, const void* q, const void* k, int64_t ksh, int64_t kst) {
+  if (g_force_path.load() == 1) return false;
+  if (s.dtype != STRUCTKV_DTYPE_BF16) return false;
+  if (s.head_dim != 64 && s.head_dim != 128) return false;
+  if ((((uintptr_t)q | (uintptr_t)k) & 15) != 0) return false;
+  if ((ksh % 8) != 0 || (kst % 8) != 0) return false;
+  return true;
+}
+
+structkv_status run_score(const structkv_shape* shape, const void* q_win, const void* k, int64_t ksh,
+                          int64_t kst, const SeqTable& seq_in, float* indeg, float* entropy,
+                          float* ent_head_out, float* probs, void* ws, size_t ws_bytes, hipStream_t st,
+                          int step_mask = 15) {
+  const structkv_shape& s = *shape;
+  SeqTable seq = seq_in;
+  const int B = seq.batch;
+  const int64_t total = seq.cu[B];
+  ScorePlan p;
+  make_plan(s, &seq, B, total, mfma_eligible(s, q_win, k, ksh, kst), &p);
+  if (p.total_bytes > ws_bytes)
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, p.total_bytes);
+  if ((int64_t)s.n_kv_heads * p.RC * p.n_chunks >= ((int64_t)1 << 31))
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "too many workgroups for one launch");
+  seq.chunk_start[0] = 0;
+  for (int b = 0; b < B; ++b) {
+    const int64_t c = seq.chunk_start[b] + ceil_div(seq.cu[b + 1] - seq.cu[b], p.KC);
+    if (c >= ((int64_t)1 << 31)) return fail(STRUCTKV_ERR_UNSUPPORTED, "too many key chunks");
+    seq.chunk_start[b + 1] = (int32_t)c;
+  }
+  uint8_t* w8 = (uint8_t*)ws;
+  float* stats = (float*)(w8 + p.off_stats);
+  float* lse2 = (float*)(w8 + p.off_lse);
+  float* colsum = (float*)(w8 + p.off_colsum);
+  float* ent_head = ent_head_out ? ent_head_out : (float*)(w8 + p.off_enthead);
+  const float scale = s.scale > 0.f ? s.scale : 1.0f / std::sqrt((float)s.head_dim);
+  const float c2 = (float)((double)scale * 1.4426950408889634);
+  auto pass = p.path == 0 ? launch_score_mfma : launch_score_simt;
+  if (step_mask & 1)
+    SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, nullptr, 1, st));
+  if (step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, ent_head, st));
+  if (step_mask & 4)
+    SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, probs, 2, st));
+  if (step_mask & 8)
+    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, ent_head, entropy, st));
+  return STRUCTKV_OK;
+}
+
+}  // namespace
+}  // namespace skv
+
+using namespace skv;
+
+extern "C" {
+
+const char* structkv_last_error(void) { return g_err; }
+
+int32_t structkv_version(void) { return 100; }
+
+int32_t structkv_debug_force_path(int32_t path) { return g_force_path.exchange(path == 1 ? 1 : 0); }
+
+size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
+  if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;
+  size_t need = topk_workspace_bytes(batch, total_tokens);
+  if (shape) {
+    if (check_shape(shape) != STRUCTKV_OK) return 0;
+    for (int path = 0; path < 2; ++path) {
+      ScorePlan p;
+      make_plan(*shape, nullptr, batch, total_tokens, path == 0, &p);
+      if (p.total_bytes > need) need = p.total_bytes;
+    }
+  }
+  return align_up(need, 256);
+}
+
+static structkv_status score_layer_impl(const structkv_shape* shape, const void* q_win, const void* k,
+                                        int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                        const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
+                                        float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
+                                        void* stream, int step_mask) {
+  clear_error();
+  structkv_status st = check_shape(shape);
+  if (st != STRUCTKV_OK) return st;
+  SeqTable seq;
+  st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (batch == 0) return STRUCTKV_OK;
+  const int64_t total = seq.cu[batch];
+  if (!q_win || !entropy_out) return fail(STRUCTKV_ERR_INVALID_ARG, "q_win or entropy_out is NULL");
+  if (total > 0 && (!k || !indeg_out)) return fail(STRUCTKV_ERR_INVALID_ARG, "k or indeg_out is NULL");
+  if (k_stride_tok < shape->head_dim)
+    return fail(STRUCTKV_ERR_INVALID_ARG, "k_stride_tok (%lld) < head_dim", (long long)k_stride_tok);
+  if (shape->n_kv_heads > 1 && k_stride_head < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "k_stride_head < 0");
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    if (shape->causal && n != 0 && n < shape->window)
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: causal scoring needs n (%lld) >= window (%d)", b,
+                  (long long)n, shape->window);
+  }
+  if (!workspace || ((uintptr_t)workspace & 255))
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg_out, entropy_out,
+                   entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask);
+}
+
+structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
+                                     int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                     const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
+                                     float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15);
+}
+
+structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,
+                                           int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                           const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
+                                           float* entropy_per_head_out, void* workspace,
+                                           size_t workspace_bytes, void* stream, int32_t step_mask) {
+  return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, step_mask & 15);
+}
+
+structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_win, const void* k,
+                                     int64_t k_stride_head, int64_t k_stride_tok, int64_t n,
+                                     float* probs_out, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  clear_error();
+  structkv_status st = check_shape(shape);
+  if (st != STRUCTKV_OK) return st;
+  if (n < 1 || (shape->causal && n < shape->window)) return fail(STRUCTKV_ERR_INVALID_ARG, "bad n");
+  if ((int64_t)shape->n_q_heads * shape->window * n > ((int64_t)1 << 26))
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "H_q*w*n exceeds 2^26");
+  if (!q_win || !k || !probs_out) return fail(STRUCTKV_ERR_INVALID_ARG, "NULL pointer");
+  if (!workspace || ((uintptr_t)workspace & 255))
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  // indeg / entropy land in scratch behind the scoring workspace
+  const size_t base = structkv_workspace_bytes(shape, 1, n);
+  const size_t extra = align_up(sizeof(float) * (size_t)n, 256) + 256;
+  if (workspace_bytes < base + extra)
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, debug_probs needs %zu", workspace_bytes,
+                base + extra);
+  const int64_t cu[2] = {0, n};
+  SeqTable seq;
+  st = check_cu(1, cu, &seq);
+  if (st != STRUCTKV_OK) return st;
+  float* indeg = (float*)((uint8_t*)workspace + base);
+  float* ent = (float*)((uint8_t*)workspace + base + align_up(sizeof(float) * (size_t)n, 256));
+  return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg, ent, nullptr, probs_out,
+                   workspace, base, (hipStream_t)stream);
+}
+
+structkv_status structkv_accumulate_centrality(float* centrality, const float* indeg, int64_t total_tokens,
+                                               float lambda, float inv_w, void* stream) {
+  clear_error();
+  if (total_tokens < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "total_tokens < 0");
+  if (!(lambda > 0.f && lambda <= 1.f)) return fail(STRUCTKV_ERR_INVALID_ARG, "lambda must be in (0,1]");
+  if (!(inv_w > 0.f) || !std::isfinite(inv_w)) return fail(STRUCTKV_ERR_INVALID_ARG, "inv_w must be > 0");
+  if (total_tokens == 0) return STRUCTKV_OK;
+  if (!centrality || !indeg) return fail(STRUCTKV_ERR_INVALID_ARG, "NULL pointer");
+  if ((((uintptr_t)centrality | (uintptr_t)indeg) & 3) != 0)
+    return fail(STRUCTKV_ERR_INVALID_ARG, "pointers must be 4-byte aligned");
+  if (ceil_div(total_tokens, 256) >= ((int64_t)1 << 31))
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "total_tokens too large for one launch");
+  SKV_HIP_CHECK(launch_accumulate(centrality, indeg, total_tokens, lambda, inv_w, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_select_topk(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                     const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  SeqTable seq;
+  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (batch == 0) return STRUCTKV_OK;
+  if (!k_per_seq) return fail(STRUCTKV_ERR_INVALID_ARG, "k_per_seq is NULL");
+  if (keep_tail < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "keep_tail < 0");
+  int64_t out = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    if (keep_tail > n)
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: keep_tail (%d) > n (%lld)", b, keep_tail, (long long)n);
+    if (k_per_seq[b] < 0 || k_per_seq[b] > n - keep_tail)
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: k (%lld) outside [0, n - keep_tail = %lld]", b,
+                  (long long)k_per_seq[b], (long long)(n - keep_tail));
+    seq.k[b] = (int32_t)k_per_seq[b];
+    seq.out_off[b] = out;
+    out += k_per_seq[b] + keep_tail;
+  }
+  seq.out_off[batch] = out;
+  if (out == 0) return STRUCTKV_OK;
+  if (!scores || !idx_out) return fail(STRUCTKV_ERR_INVALID_ARG, "scores or idx_out is NULL");
+  if (!workspace || ((uintptr_t)workspace & 255))
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  const size_t need = topk_workspace_bytes(batch, seq.cu[batch]);
+  if (workspace_bytes < need)
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, top-k needs %zu", workspace_bytes, need);
+  SKV_HIP_CHECK(launch_topk(scores, seq, keep_tail, idx_out, workspace, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t src_stride_head,
+                                   int64_t src_stride_tok, void* k_dst, void* v_dst, int64_t dst_stride_head,
+                                   int64_t dst_stride_tok, int32_t n_kv_heads, int32_t head_dim,
+                                   int32_t elem_bytes, int32_t batch, const int64_t* cu_seqlens,
+                                   const int64_t* rows_per_seq, const int32_t* idx, void* stream) {
+  clear_error();
+  SeqTable seq;
+  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (n_kv_heads < 1 || head_dim < 1) return fail(STRUCTKV_ERR_INVALID_ARG, "n_kv_heads and head_dim must be >= 1");
+  if (n_kv_heads > 65535) return fail(STRUCTKV_ERR_UNSUPPORTED, "n_kv_heads > 65535");
+  if (elem_bytes != 2 && elem_bytes != 4) return fail(STRUCTKV_ERR_UNSUPPORTED, "elem_bytes must be 2 or 4");
+  if (batch == 0) return STRUCTKV_OK;
+  if (!rows_per_seq) return fail(STRUCTKV_ERR_INVALID_ARG, "rows_per_seq is NULL");
+  if (src_stride_tok < head_dim || dst_stride_tok < head_dim)
+    return fail(STRUCTKV_ERR_INVALID_ARG, "token strides must be >= head_dim");
+  if (src_stride_head < 0 || dst_stride_head < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "negative head stride");
+  int64_t out = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    if (rows_per_seq[b] < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "rows_per_seq[%d] < 0", b);
+    if (rows_per_seq[b] > 0 && n == 0)
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d is empty but rows_per_seq is %lld", b,
+                  (long long)rows_per_seq[b]);
+    seq.out_off[b] = out;
+    out += rows_per_seq[b];
+  }
+  seq.out_off[batch] = out;
+  if (out == 0) return STRUCTKV_OK;
+  if (!idx) return fail(STRUCTKV_ERR_INVALID_ARG, "idx is NULL");
+  if ((k_src == nullptr) != (k_dst == nullptr) || (v_src == nullptr) != (v_dst == nullptr))
+    return fail(STRUCTKV_ERR_INVALID_ARG, "src/dst of a pair must both be given or both be NULL");
+  if (!k_src && !v_src) return STRUCTKV_OK;
+  const uintptr_t ptrs = (uintptr_t)k_src | (uintptr_t)v_src | (uintptr_t)k_dst | (uintptr_t)v_dst;
+  if (ptrs & (uintptr_t)(elem_bytes - 1)) return fail(STRUCTKV_ERR_INVALID_ARG, "pointers not aligned to the element size");
+  const int64_t e = elem_bytes;
+  if (ceil_div(out * head_dim * e / 2, 1024) >= ((int64_t)1 << 31))
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "too many rows for one launch");
+  SKV_HIP_CHECK(launch_gather(k_src, v_src, src_stride_head * e, src_stride_tok * e, k_dst, v_dst,
+                              dst_stride_head * e, dst_stride_tok * e, n_kv_heads, head_dim * elem_bytes, seq,
+                              idx, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
+}  // extern "C"

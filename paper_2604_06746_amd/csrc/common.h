@@ -1,0 +1,72 @@
+// Internal declarations shared by the libstructkv translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/structkv.h"
+
+namespace skv {
+
+// Record a thread-local error message and return the status.
+structkv_status fail(structkv_status st, const char* fmt, ...);
+void clear_error();
+
+#define SKV_HIP_CHECK(expr)                                                              \
+  do {                                                                                   \
+    hipError_t _e = (expr);                                                              \
+    if (_e != hipSuccess)                                                                \
+      return skv::fail(STRUCTKV_ERR_HIP, "%s: %s", #expr, hipGetErrorString(_e));        \
+  } while (0)
+
+constexpr int kMaxBatch = STRUCTKV_MAX_BATCH;
+
+// Per-sequence table passed by value in kernel arguments (host arrays never touch the device heap).
+struct SeqTable {
+  int64_t cu[kMaxBatch + 1];        // token offsets
+  int64_t out_off[kMaxBatch + 1];   // output-row offsets (top-k / gather)
+  int32_t k[kMaxBatch];             // top-k budget
+  int32_t chunk_start[kMaxBatch + 1]; // cumulative key-chunk counts (scoring) / block counts (top-k)
+  int32_t batch;
+};
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- scoring plan: how one structkv_score_layer call is cut into workgroups ----------------
+struct ScorePlan {
+  int path;          // 0 = bf16 MFMA, 1 = SIMT
+  int R;             // query rows per KV head: (H_q/G) * w
+  int RPC;           // rows per row-chunk (a workgroup's share of R)
+  int RC;            // row-chunks per KV head
+  int KC;            // keys per key-chunk (one workgroup)
+  int WK;            // partial statistics written per (row-chunk, key-chunk)
+  int RB, WR;        // MFMA path: 32-row blocks per wave, waves along rows
+  int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
+  // workspace carve (byte offsets)
+  size_t off_stats, off_lse, off_colsum, off_enthead, total_bytes;
+};
+
+// Launchers (each enqueues on `stream`, returns hipGetLastError()).
+hipError_t launch_score_mfma(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                             const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
+                             float* stats, const float* lse2, float* colsum, int64_t total,
+                             float* probs, int pass, hipStream_t st);
+hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                             const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
+                             float* stats, const float* lse2, float* colsum, int64_t total,
+                             float* probs, int pass, hipStream_t st);
+hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                                const float* stats, float* lse2, float* ent_head, hipStream_t st);
+hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                               const float* colsum, int64_t total, float* indeg,
+                               const float* ent_head, float* entropy, hipStream_t st);
+hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st);
+hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
+                       void* ws, hipStream_t st);
+size_t topk_workspace_bytes(int batch, int64_t total_tokens);
+hipError_t launch_gather(const void* k_src, const void* v_src, int64_t ssh, int64_t sst, void* k_dst,
+                         void* v_dst, int64_t dsh, int64_t dst_, int G, int row_bytes,
+                         const SeqTable& seq, const int32_t* idx, hipStream_t st);
+
+}  // namespace skv

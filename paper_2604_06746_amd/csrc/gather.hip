@@ -1,0 +1,80 @@
+// Index-driven K/V row gather (paper Alg. 1 line 17: the decoupled cache store).
+// One thread moves one vector unit (16, 4 or 2 bytes) of one row; consecutive threads cover a row,
+// then the next row, so reads are 256-byte row bursts and writes are fully contiguous.  Each thread
+// has four independent row copies in flight.
+#include "common.h"
+
+namespace skv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+template <typename V>
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(
+    const uint8_t* __restrict__ src0, const uint8_t* __restrict__ src1, uint8_t* __restrict__ dst0,
+    uint8_t* __restrict__ dst1, int64_t ssh, int64_t sst, int64_t dsh, int64_t dst_tok, int units_per_row,
+    int64_t total_units, SeqTable seq, const int32_t* __restrict__ idx) {
+  const int g = blockIdx.y;
+  const uint8_t* src = (blockIdx.z == 0 ? src0 : src1) + (int64_t)g * ssh;
+  uint8_t* dst = (blockIdx.z == 0 ? dst0 : dst1) + (int64_t)g * dsh;
+  const int64_t base = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  V val[kUnroll];
+  int64_t doff[kUnroll];
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i) {
+    const int64_t lin = base + (int64_t)i * kThreads;
+    doff[i] = -1;
+    if (lin < total_units) {
+      const int64_t row = lin / units_per_row;
+      const int u = (int)(lin - row * units_per_row);
+      int b = 0;
+      for (int bb = 1; bb < seq.batch; ++bb) b += row >= seq.out_off[bb];
+      const int64_t n = seq.cu[b + 1] - seq.cu[b];
+      int64_t j = idx[row];
+      if (j < 0 || j >= n) j = 0;
+      val[i] = *reinterpret_cast<const V*>(src + (seq.cu[b] + j) * sst + (int64_t)u * sizeof(V));
+      doff[i] = row * dst_tok + (int64_t)u * sizeof(V);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kUnroll; ++i)
+    if (doff[i] >= 0) *reinterpret_cast<V*>(dst + doff[i]) = val[i];
+}
+
+}  // namespace
+
+// strides in BYTES here
+hipError_t launch_gather(const void* k_src, const void* v_src, int64_t ssh, int64_t sst, void* k_dst,
+                         void* v_dst, int64_t dsh, int64_t dst_tok, int G, int row_bytes,
+                         const SeqTable& seq, const int32_t* idx, hipStream_t st) {
+  const int64_t rows = seq.out_off[seq.batch];
+  if (rows == 0 || G == 0) return hipSuccess;
+  const uint8_t* s0 = (const uint8_t*)k_src;
+  const uint8_t* s1 = (const uint8_t*)v_src;
+  uint8_t* d0 = (uint8_t*)k_dst;
+  uint8_t* d1 = (uint8_t*)v_dst;
+  int nz = 2;
+  if (s0 == nullptr) { s0 = s1; d0 = d1; nz = 1; }
+  else if (s1 == nullptr) { nz = 1; }
+  if (s0 == nullptr) return hipSuccess;
+  uintptr_t bits = (uintptr_t)s0 | (uintptr_t)d0 | (uintptr_t)ssh | (uintptr_t)sst | (uintptr_t)dsh |
+                   (uintptr_t)dst_tok | (uintptr_t)row_bytes;
+  if (nz == 2) bits |= (uintptr_t)s1 | (uintptr_t)d1;
+  const int vec = (bits & 15) == 0 ? 16 : ((bits & 3) == 0 ? 4 : 2);
+  const int upr = row_bytes / vec;
+  const int64_t total_units = rows * upr;
+  dim3 grid((unsigned)ceil_div(total_units, kThreads * kUnroll), (unsigned)G, (unsigned)nz), blk(kThreads);
+  if (vec == 16)
+    hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh, dst_tok,
+                       upr, total_units, seq, idx);
+  else if (vec == 4)
+    hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh,
+                       dst_tok, upr, total_units, seq, idx);
+  else
+    hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh,
+                       dst_tok, upr, total_units, seq, idx);
+  return hipGetLastError();
+}
+
+}  // namespace skv

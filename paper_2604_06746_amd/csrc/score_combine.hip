@@ -1,0 +1,136 @@
+// Small kernels around the two scoring passes:
+//   combine : merge the per-key-chunk softmax statistics of every query row into
+//             lse2 = M + log2 Z (what pass 2 normalises with) and the row entropies of Eq. 4,
+//             averaged over the window rows of each head.
+//   reduce  : D_j = sum over KV heads / row-chunks of the pass-2 column sums (Eq. 2 without 1/w),
+//             plus the mean over heads that finishes Eq. 4.
+//   accumulate : C <- lambda C + inv_w D   (Alg. 1 line 6 / Eq. 3).
+#include "common.h"
+
+namespace skv {
+namespace {
+
+constexpr float kLn2 = 0.6931471805599453f;
+
+// one workgroup per (sequence b, KV head g); thread <-> query row of the group
+__global__ __launch_bounds__(256) void score_combine_kernel(
+    SeqTable seq, int Hq, int G, int w, int R, int RPC, int RC, int WK, int64_t n_chunks,
+    const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ ent_head) {
+  extern __shared__ float row_ent[];  // [R]
+  const int b = blockIdx.x / G, g = blockIdx.x % G;
+  const int64_t c0 = seq.chunk_start[b], c1 = seq.chunk_start[b + 1];
+  const int gs = Hq / G;
+  for (int row = threadIdx.x; row < R; row += blockDim.x) {
+    const int rc = row / RPC, rr = row % RPC;
+    const int grc = g * RC + rc;
+    float M = -1.0e30f, Z = 0.f, E = 0.f;
+    for (int64_t c = c0; c < c1; ++c) {
+      for (int wk = 0; wk < WK; ++wk) {
+        const float* sp = stats + ((((int64_t)grc * n_chunks + c) * WK + wk) * 3) * RPC + rr;
+        const float M2 = sp[0], Z2 = sp[RPC], E2 = sp[2 * RPC];
+        const float Mn = fmaxf(M, M2);
+        const float d1 = M - Mn, d2 = M2 - Mn;
+        const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
+        E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
+        Z = Z * f1 + Z2 * f2;
+        M = Mn;
+      }
+    }
+    float ent = 0.f, l2 = 0.f;
+    if (c1 > c0) {
+      const float lz = __log2f(Z);
+      l2 = M + lz;
+      ent = kLn2 * (lz - E / Z);   // -sum a ln a  with a = 2^(x-M)/Z
+    }
+    lse2[(int64_t)b * G * R + (int64_t)g * R + row] = l2;
+    row_ent[row] = ent;
+  }
+  __syncthreads();
+  for (int hl = threadIdx.x; hl < gs; hl += blockDim.x) {
+    float s = 0.f;
+    for (int i = 0; i < w; ++i) s += row_ent[hl * w + i];
+    ent_head[(int64_t)b * Hq + g * gs + hl] = s / (float)w;
+  }
+}
+
+__global__ __launch_bounds__(256) void score_reduce_kernel(
+    const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
+    const float* __restrict__ ent_head, float* __restrict__ entropy, int B, int Hq, int vec) {
+  const int64_t i4 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (vec && i4 + 3 < total) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < GRC; ++p) {
+      const float4 v = *reinterpret_cast<const float4*>(colsum + (int64_t)p * total + i4);
+      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    }
+    *reinterpret_cast<float4*>(indeg + i4) = a;
+  } else {
+    for (int64_t i = i4; i < min(i4 + 4, total); ++i) {
+      float a = 0.f;
+      for (int p = 0; p < GRC; ++p) a += colsum[(int64_t)p * total + i];
+      indeg[i] = a;
+    }
+  }
+  if (threadIdx.x == 0) {
+    for (int b = blockIdx.x; b < B; b += gridDim.x) {
+      float s = 0.f;
+      for (int h = 0; h < Hq; ++h) s += ent_head[(int64_t)b * Hq + h];
+      entropy[b] = s / (float)Hq;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, const float* __restrict__ d,
+                                                         int64_t n, float lambda, float inv_w, int vec) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (vec) {
+    const int64_t i4 = i * 4;
+    if (i4 + 3 < n) {
+      float4 cv = *reinterpret_cast<float4*>(c + i4);
+      const float4 dv = *reinterpret_cast<const float4*>(d + i4);
+      cv.x = fmaf(lambda, cv.x, inv_w * dv.x);
+      cv.y = fmaf(lambda, cv.y, inv_w * dv.y);
+      cv.z = fmaf(lambda, cv.z, inv_w * dv.z);
+      cv.w = fmaf(lambda, cv.w, inv_w * dv.w);
+      *reinterpret_cast<float4*>(c + i4) = cv;
+    } else {
+      for (int64_t j = i4; j < n; ++j) c[j] = fmaf(lambda, c[j], inv_w * d[j]);
+    }
+  } else if (i < n) {
+    c[i] = fmaf(lambda, c[i], inv_w * d[i]);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                                const float* stats, float* lse2, float* ent_head, hipStream_t st) {
+  const int blocks = seq.batch * s.n_kv_heads;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(score_combine_kernel, dim3(blocks), dim3(256), sizeof(float) * p.R, st, seq,
+                     s.n_q_heads, s.n_kv_heads, s.window, p.R, p.RPC, p.RC, p.WK, p.n_chunks, stats, lse2,
+                     ent_head);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                               const float* colsum, int64_t total, float* indeg, const float* ent_head,
+                               float* entropy, hipStream_t st) {
+  int64_t blocks = ceil_div(ceil_div(total, 4), 256);
+  if (blocks == 0) blocks = 1;
+  const int vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum) & 15) == 0;
+  hipLaunchKernelGGL(score_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
+                     s.n_kv_heads * p.RC, total, indeg, ent_head, entropy, seq.batch, s.n_q_heads, vec);
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const int vec = (((uintptr_t)c | (uintptr_t)d) & 15) == 0;
+  const int64_t work = vec ? ceil_div(n, 4) : n;
+  hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)ceil_div(work, 256)), dim3(256), 0, st, c, d, n,
+                     lambda, inv_w, vec);
+  return hipGetLastError();
+}
+
+}  // namespace skv

@@ -1,0 +1,73 @@
+"""Buffer management for a per-layer StructKV scoring sweep (Alg. 1 lines 4, 6, 16, 17).
+
+Owns the torch buffers and calls the C ABI in order; no arithmetic happens here.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class LayerSweep:
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, window: int, dtype: torch.dtype,
+                 seq_lens: Sequence[int], k_per_seq: Sequence[int], lam: float = 0.9, causal: bool = False,
+                 scale: float = 0.0, n_layers_out: int = 1, device="cuda"):
+        self.Hq, self.G, self.d, self.w = n_q_heads, n_kv_heads, head_dim, window
+        self.seq_lens = [int(n) for n in seq_lens]
+        self.k_per_seq = [int(k) for k in k_per_seq]
+        self.batch = len(self.seq_lens)
+        self.cu = [0]
+        for n in self.seq_lens:
+            self.cu.append(self.cu[-1] + n)
+        self.total = self.cu[-1]
+        self.lam = float(lam)
+        self.keep_tail = window
+        self.rows_per_seq = [k + self.keep_tail for k in self.k_per_seq]
+        self.rows = sum(self.rows_per_seq)
+        code = {torch.float32: B.STRUCTKV_DTYPE_F32, torch.bfloat16: B.STRUCTKV_DTYPE_BF16}[dtype]
+        self.shape = B.make_shape(n_q_heads, n_kv_heads, head_dim, window, code, causal, scale)
+        ws_bytes = B.structkv_workspace_bytes(self.shape, self.batch, self.total)
+        dev = torch.device(device)
+        self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        self.indeg = torch.empty(self.total, dtype=torch.float32, device=dev)
+        self.centrality = torch.zeros(self.total, dtype=torch.float32, device=dev)
+        self.entropy = torch.empty(max(self.batch, 1), dtype=torch.float32, device=dev)
+        self.entropy_per_head = torch.empty(max(self.batch, 1), n_q_heads, dtype=torch.float32, device=dev)
+        self.idx_kv = torch.empty(max(self.rows, 1), dtype=torch.int32, device=dev)
+        self.idx_struct = torch.empty(max(self.rows, 1), dtype=torch.int32, device=dev)
+        self.k_cache = torch.empty(n_layers_out, n_kv_heads, max(self.rows, 1), head_dim, dtype=dtype, device=dev)
+        self.v_cache = torch.empty_like(self.k_cache)
+
+    def reset(self) -> None:
+        self.centrality.zero_()
+
+    def score(self, q_win: torch.Tensor, k: torch.Tensor, stream=None) -> None:
+        B.structkv_score_layer(self.shape, q_win, k, self.cu, self.indeg, self.entropy,
+                               self.entropy_per_head, self.workspace, stream)
+
+    def accumulate(self, stream=None) -> None:
+        B.structkv_accumulate_centrality(self.centrality, self.indeg, self.lam, 1.0 / self.w, stream)
+
+    def select_kv(self, stream=None) -> None:
+        """Eq. 13: per-layer storage indices from this layer's scores."""
+        B.structkv_select_topk(self.indeg, self.cu, self.k_per_seq, self.keep_tail, self.idx_kv,
+                               self.workspace, stream)
+
+    def select_struct(self, k_per_seq: Optional[Sequence[int]] = None, stream=None) -> None:
+        """Eq. 10: propagation indices from the accumulated centrality."""
+        B.structkv_select_topk(self.centrality, self.cu, k_per_seq or self.k_per_seq, self.keep_tail,
+                               self.idx_struct, self.workspace, stream)
+
+    def gather(self, k: torch.Tensor, v: torch.Tensor, slot: int = 0, stream=None) -> None:
+        B.structkv_gather_kv(k, v, self.k_cache[slot], self.v_cache[slot], self.cu, self.rows_per_seq,
+                             self.idx_kv, stream)
+
+    def layer(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, slot: int = 0, stream=None) -> None:
+        """One pass of the hot path over one layer: score -> accumulate -> select -> gather."""
+        self.score(q_win, k, stream)
+        self.accumulate(stream)
+        self.select_kv(stream)
+        self.gather(k, v, slot, stream)

@@ -1,0 +1,122 @@
+"""CPU-only checks of the C ABI: the library loads, exports what the header declares, and rejects
+bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    lib = os.path.join(ROOT, "paper_2604_06746_amd", "libstructkv.so")
+    if not os.path.exists(lib):
+        from paper_2604_06746_amd import build
+        build.build(verbose=False)
+    from paper_2604_06746_amd import binding
+    return binding
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "structkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(structkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(B):
+    names = _declared()
+    assert {"structkv_score_layer", "structkv_accumulate_centrality", "structkv_select_topk",
+            "structkv_gather_kv"} <= set(names)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B.EXPORTS)
+    assert B.structkv_version() >= 100
+
+
+def test_workspace_query(B):
+    s = B.make_shape(32, 8, 128, 64, B.STRUCTKV_DTYPE_BF16)
+    a = B.structkv_workspace_bytes(s, 1, 131072)
+    b = B.structkv_workspace_bytes(s, 1, 262144)
+    assert 0 < a < b and a % 256 == 0
+    assert 0 < B.structkv_workspace_bytes(None, 8, 500000) < a
+    assert B.structkv_workspace_bytes(s, -1, 10) == 0
+    assert B.structkv_workspace_bytes(s, B.STRUCTKV_MAX_BATCH + 1, 10) == 0
+    bad = B.make_shape(32, 5, 128, 64, B.STRUCTKV_DTYPE_BF16)
+    assert B.structkv_workspace_bytes(bad, 1, 10) == 0
+
+
+def _status(B, fn, *args):
+    st = fn(*args)
+    return st, B.structkv_last_error()
+
+
+def test_invalid_arguments_are_rejected_on_the_host(B):
+    lib = B._lib
+    i64 = ctypes.c_int64
+    cu = (i64 * 2)(0, 100)
+    fake = ctypes.c_void_p(4096)      # never dereferenced: validation fails first
+    ws_bytes = 1 << 20
+
+    def score(shape, cu_arr=cu, batch=1, ws=fake, wsb=ws_bytes, kst=128):
+        return lib.structkv_score_layer(ctypes.byref(shape), fake, fake, 100 * 128, kst, batch, cu_arr, fake,
+                                        fake, None, ws, wsb, None)
+
+    ok_shape = B.make_shape(8, 2, 128, 32, B.STRUCTKV_DTYPE_BF16)
+    assert score(B.make_shape(8, 3, 128, 32, 1)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert "divide" in B.structkv_last_error()
+    assert score(B.make_shape(8, 2, 128, 0, 1)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(B.make_shape(8, 2, 1024, 32, 1)) == B.STRUCTKV_ERR_UNSUPPORTED
+    assert score(B.make_shape(8, 2, 128, 32, 7)) == B.STRUCTKV_ERR_UNSUPPORTED
+    assert score(B.make_shape(8, 2, 128, 32, 1, scale=-1.0)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(ok_shape, cu_arr=(i64 * 2)(1, 100)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(ok_shape, cu_arr=(i64 * 3)(0, 100, 50), batch=2) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(ok_shape, batch=B.STRUCTKV_MAX_BATCH + 1) == B.STRUCTKV_ERR_UNSUPPORTED
+    assert score(ok_shape, kst=64) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(ok_shape, ws=None) == B.STRUCTKV_ERR_WORKSPACE
+    assert score(ok_shape, ws=ctypes.c_void_p(4096 + 8)) == B.STRUCTKV_ERR_WORKSPACE
+    assert score(ok_shape, wsb=16) == B.STRUCTKV_ERR_WORKSPACE
+    assert "needs" in B.structkv_last_error()
+    causal = B.make_shape(8, 2, 128, 32, 1, causal=True)
+    assert score(causal, cu_arr=(i64 * 2)(0, 10)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert score(ok_shape, batch=0) == B.STRUCTKV_OK and B.structkv_last_error() == ""
+
+    acc = lib.structkv_accumulate_centrality
+    assert acc(fake, fake, 10, 0.0, 0.1, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert acc(fake, fake, 10, 1.5, 0.1, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert acc(fake, fake, 10, 0.9, 0.0, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert acc(None, fake, 10, 0.9, 0.1, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert acc(fake, fake, -1, 0.9, 0.1, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert acc(None, None, 0, 0.9, 0.1, None) == B.STRUCTKV_OK
+
+    topk = lib.structkv_select_topk
+    assert topk(fake, 1, cu, (i64 * 1)(101), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(90), 32, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(-1), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(10), -1, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(10), 200, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(10), 0, fake, fake, 8, None) == B.STRUCTKV_ERR_WORKSPACE
+    assert topk(fake, 1, cu, (i64 * 1)(10), 0, None, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert topk(fake, 1, cu, (i64 * 1)(0), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_OK   # nothing to do
+
+    gat = lib.structkv_gather_kv
+    rows = (i64 * 1)(5)
+    assert gat(fake, fake, 12800, 128, fake, fake, 640, 128, 8, 128, 3, 1, cu, rows, fake, None) == B.STRUCTKV_ERR_UNSUPPORTED
+    assert gat(fake, fake, 12800, 64, fake, fake, 640, 128, 8, 128, 2, 1, cu, rows, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert gat(fake, None, 12800, 128, None, fake, 640, 128, 8, 128, 2, 1, cu, rows, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert gat(fake, fake, 12800, 128, fake, fake, 640, 128, 8, 128, 2, 1, cu, rows, None, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert gat(fake, fake, 12800, 128, fake, fake, 640, 128, 8, 128, 2, 1, cu, (i64 * 1)(-2), fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert gat(fake, fake, 12800, 128, fake, fake, 640, 128, 8, 128, 2, 1, cu, (i64 * 1)(0), fake, None) == B.STRUCTKV_OK
+
+
+def test_binding_raises_with_message(B):
+    import torch
+    s = B.make_shape(8, 3, 128, 32, B.STRUCTKV_DTYPE_BF16)
+    q = torch.zeros(1, 8, 32, 128, dtype=torch.bfloat16)
+    k = torch.zeros(2, 100, 128, dtype=torch.bfloat16)
+    out = torch.zeros(100)
+    with pytest.raises(B.StructKVError) as e:
+        B.structkv_score_layer(s, q, k, [0, 100], out, out, None, out, stream=0)
+    assert e.value.status == B.STRUCTKV_ERR_INVALID_ARG and "divide" in str(e.value)

@@ -1,0 +1,326 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element.
+
+Tolerances (bf16 inputs, fp32 accumulation; derived in the design doc):
+  in-degree D, centrality C : |gpu - ref| <= 1e-3 * max(|ref|, 1e-6 * mean|ref|)
+  entropy                   : rel 1e-3 (abs 1e-4 below 0.1)
+  fp32 inputs               : the same checks at 2e-5
+  top-k on identical fp32 scores, gather : bit-exact
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from helpers import (to_oracle_array, _tol, assert_close_floor, assert_entropy, make_sweep, oracle_layer,
+                     sweep_against_oracle)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2604_06746_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def sweep_mod():
+    from paper_2604_06746_amd import sweep
+    return sweep
+
+
+SMALL = ["s_bf16_gqa4", "s_bf16_w64", "s_bf16_d64", "s_bf16_ragged", "s_f32_w8", "s_f32_ragged", "c1_tiny"]
+
+
+# ------------------------------------------------------------------ attention rows (MFMA lane layout)
+
+@pytest.mark.parametrize("name", ["s_bf16_gqa4", "s_bf16_w64", "s_bf16_d64", "s_f32_w8"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("force_simt", [False, True])
+def test_attention_rows_match_oracle(B, oracle, name, causal, force_simt):
+    wl = workloads.WORKLOADS[name]
+    n = wl.seq_lens[0]
+    x = workloads.make_layer(wl, 0, "cuda")
+    code = B.STRUCTKV_DTYPE_F32 if wl.dtype == "f32" else B.STRUCTKV_DTYPE_BF16
+    shape = B.make_shape(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, code, causal)
+    ws = torch.empty(B.structkv_workspace_bytes(shape, 1, n) + 4 * n + 1024, dtype=torch.uint8, device="cuda")
+    probs = torch.full((wl.n_q_heads, wl.window, n), -1.0, dtype=torch.float32, device="cuda")
+    prev = B.structkv_debug_force_path(1 if force_simt else 0)
+    try:
+        B.structkv_debug_probs(shape, x.q_win, x.k, n, probs, ws)
+        torch.cuda.synchronize()
+    finally:
+        B.structkv_debug_force_path(prev)
+    _, _, _, p_ref = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads,
+                                        wl.n_kv_heads, wl.head_dim, wl.window, [n], causal=causal,
+                                        want_probs=True)
+    got = probs.cpu().numpy().astype(np.float64)
+    assert np.abs(got.sum(-1) - 1.0).max() < 1e-4          # every softmax row sums to 1
+    tol = _tol(wl)
+    assert np.abs(got - p_ref[0]).max() <= tol * max(p_ref[0].max(), 1e-3)
+    assert_close_floor(got, p_ref[0], 5 * tol, "probs")
+    if causal:
+        w = wl.window
+        for i in range(w):
+            assert np.all(got[:, i, n - w + i + 1:] == 0.0)
+
+
+# ------------------------------------------------------------------ score_layer (Eq. 1, 2, 4)
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("force_simt", [False, True])
+def test_score_layer_matches_oracle(B, sweep_mod, oracle, name, causal, force_simt):
+    wl = workloads.WORKLOADS[name]
+    if causal and min(wl.seq_lens) < wl.window:
+        pytest.skip("causal needs n >= w")
+    sw = make_sweep(sweep_mod, wl, causal)
+    prev = B.structkv_debug_force_path(1 if force_simt else 0)
+    try:
+        for layer in range(min(wl.n_layers, 2)):
+            x = workloads.make_layer(wl, layer, "cuda")
+            sw.indeg.fill_(-7.0)
+            sw.score(x.q_win, x.k)
+            torch.cuda.synchronize()
+            D, ent, ent_h, _ = oracle_layer(oracle, wl, x, causal)
+            got = sw.indeg.cpu().numpy()
+            assert_close_floor(got, D, _tol(wl), "indeg layer %d" % layer)
+            off = 0
+            for n in wl.seq_lens:                       # in-degree total per sequence is w * H_q
+                assert abs(got[off:off + n].astype(np.float64).sum() - wl.window * wl.n_q_heads) < 1e-4 * wl.window * wl.n_q_heads
+                off += n
+            assert_entropy(sw.entropy.cpu().numpy()[:wl.batch], ent, _tol(wl))
+            assert_entropy(sw.entropy_per_head.cpu().numpy()[:wl.batch], ent_h, _tol(wl))
+    finally:
+        B.structkv_debug_force_path(prev)
+
+
+def test_score_layer_is_deterministic(sweep_mod):
+    wl = workloads.S_BF16_RAGGED
+    sw = make_sweep(sweep_mod, wl)
+    x = workloads.make_layer(wl, 1, "cuda")
+    sw.score(x.q_win, x.k)
+    a, ea = sw.indeg.clone(), sw.entropy.clone()
+    sw.workspace.fill_(0xAB)                               # the workspace needs no particular contents
+    sw.score(x.q_win, x.k)
+    torch.cuda.synchronize()
+    assert torch.equal(a, sw.indeg) and torch.equal(ea, sw.entropy)
+
+
+def test_score_layer_strided_k_and_explicit_scale(B, sweep_mod, oracle):
+    # K stored [total, G, d] (token-major): head stride d, token stride G*d
+    wl = workloads.S_BF16
+    x = workloads.make_layer(wl, 0, "cuda")
+    k_tok_major = x.k.permute(1, 0, 2).contiguous()
+    k_view = k_tok_major.permute(1, 0, 2)
+    assert k_view.stride() == (wl.head_dim, wl.n_kv_heads * wl.head_dim, 1)
+    sw = sweep_mod.LayerSweep(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.torch_dtype, wl.seq_lens,
+                              wl.k_per_seq, scale=0.05)
+    sw.score(x.q_win, k_view)
+    torch.cuda.synchronize()
+    D, ent, _, _ = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads,
+                                      wl.n_kv_heads, wl.head_dim, wl.window, wl.seq_lens, scale=0.05)
+    assert_close_floor(sw.indeg.cpu().numpy(), D, 1e-3, "indeg strided")
+    assert_entropy(sw.entropy.cpu().numpy(), ent, 1e-3)
+
+
+def test_uniform_attention_entropy_is_log_n(sweep_mod):
+    # all keys identical -> every row is uniform: D_j = w*H_q/n and entropy = ln n
+    n, Hq, G, d, w = 1500, 8, 2, 128, 32
+    q = torch.randn(1, Hq, w, d, device="cuda").to(torch.bfloat16)
+    k = torch.randn(G, 1, d, device="cuda").to(torch.bfloat16).expand(G, n, d).contiguous()
+    sw = sweep_mod.LayerSweep(Hq, G, d, w, torch.bfloat16, [n], [10])
+    sw.score(q, k)
+    torch.cuda.synchronize()
+    assert abs(float(sw.entropy[0]) - math.log(n)) < 1e-3 * math.log(n)
+    assert_close_floor(sw.indeg.cpu().numpy(), np.full(n, w * Hq / n), 1e-3, "uniform indeg")
+
+
+def test_large_logits_do_not_overflow(sweep_mod, oracle):
+    # a constant offset on every key shifts each row's logits by up to ~hundreds: needs the running max
+    wl = workloads.S_BF16
+    x = workloads.make_layer(wl, 0, "cuda")
+    k = (x.k.float() + 30.0).to(torch.bfloat16)
+    sw = make_sweep(sweep_mod, wl)
+    sw.score(x.q_win, k)
+    torch.cuda.synchronize()
+    D, ent, _, _ = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(k), wl.n_q_heads, wl.n_kv_heads,
+                                      wl.head_dim, wl.window, wl.seq_lens)
+    got = sw.indeg.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert_close_floor(got, D, 1e-3, "indeg shifted keys")
+    assert_entropy(sw.entropy.cpu().numpy(), ent, 1e-3)
+
+
+def test_empty_sequences_in_batch(sweep_mod, oracle):
+    Hq, G, d, w = 8, 2, 128, 32
+    lens = [0, 200, 0, 65, 0]
+    q = torch.randn(len(lens), Hq, w, d, device="cuda").to(torch.bfloat16)
+    k = torch.randn(G, sum(lens), d, device="cuda").to(torch.bfloat16)
+    v = torch.randn(G, sum(lens), d, device="cuda").to(torch.bfloat16)
+    ks = [0, 20, 0, 5, 0]
+    sw = sweep_mod.LayerSweep(Hq, G, d, w, torch.bfloat16, lens, ks)
+    sw.keep_tail = 0
+    sw.rows_per_seq = ks
+    sw.layer(q, k, v)
+    torch.cuda.synchronize()
+    D, ent, _, _ = oracle.score_layer(to_oracle_array(q), to_oracle_array(k), Hq, G, d, w, lens)
+    assert_close_floor(sw.indeg.cpu().numpy(), D, 1e-3, "indeg")
+    assert_entropy(sw.entropy.cpu().numpy(), ent, 1e-3)
+    got_d = sw.indeg.cpu().numpy()
+    ref_idx = oracle.select_topk(got_d, lens, ks, 0)
+    got_idx = sw.idx_kv.cpu().numpy()[:sum(ks)]
+    assert np.array_equal(got_idx, np.concatenate(ref_idx))
+    ref_k = oracle.gather_kv(to_oracle_array(k), ref_idx, lens)
+    assert np.array_equal(to_oracle_array(sw.k_cache[0][:, :sum(ks)]), ref_k)
+
+
+# ------------------------------------------------------------------ accumulate (Eq. 3 / Alg. 1 line 6)
+
+def test_accumulate_matches_oracle(B, oracle):
+    rng = np.random.default_rng(5)
+    for n in (1, 7, 1024, 4099):
+        for lam in (0.5, 0.9, 1.0):
+            C = rng.random(n).astype(np.float32)
+            D = (rng.random(n) * 50).astype(np.float32)
+            c = torch.tensor(C, device="cuda")
+            d = torch.tensor(D, device="cuda")
+            B.structkv_accumulate_centrality(c, d, lam, 1.0 / 32)
+            ref = C.astype(np.float64)
+            oracle.accumulate(ref, D.astype(np.float64), float(np.float32(lam)), 1.0 / 32)
+            assert np.abs(c.cpu().numpy() - ref).max() <= 2e-7 * np.abs(ref).max()
+    # unaligned views take the scalar path
+    c = torch.zeros(1001, device="cuda")[1:]
+    d = torch.ones(1001, device="cuda")[1:]
+    B.structkv_accumulate_centrality(c, d, 0.9, 0.25)
+    assert torch.all(c == 0.25)
+
+
+# ------------------------------------------------------------------ top-k (Eq. 10 / Eq. 13)
+
+def _topk_gpu(B, scores, lens, ks, tail):
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    s = torch.tensor(scores, dtype=torch.float32, device="cuda")
+    out = torch.full((max(sum(ks) + tail * len(lens), 1),), -5, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(B.structkv_workspace_bytes(None, len(lens), int(sum(lens))), 256), dtype=torch.uint8,
+                     device="cuda")
+    ws.fill_(0x5A)
+    B.structkv_select_topk(s, cu, ks, tail, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()[:sum(ks) + tail * len(lens)]
+
+
+@pytest.mark.parametrize("n,k,tail", [(1000, 100, 32), (257, 1, 0), (64, 32, 32), (50, 50, 0), (10, 0, 3),
+                                      (4096, 4000, 64), (4097, 17, 1), (20000, 2048, 32), (300000, 16384, 64),
+                                      (1, 1, 0), (33, 0, 33)])
+def test_topk_bit_identical_to_oracle(B, oracle, n, k, tail):
+    rng = np.random.default_rng(n * 31 + k)
+    for variant in ("normal", "ties", "all_equal", "tiny_range", "signed"):
+        if variant == "normal":
+            s = rng.standard_normal(n)
+        elif variant == "ties":
+            s = rng.integers(0, 5, n).astype(np.float64) * 0.25
+        elif variant == "all_equal":
+            s = np.full(n, 0.125)
+        elif variant == "tiny_range":
+            s = 1.0 + rng.integers(0, 40, n) * 2.0 ** -23      # neighbours differ in the last mantissa bits
+        else:
+            s = rng.standard_normal(n) * 10.0 ** rng.integers(-30, 30, n)
+            s[rng.integers(0, n, max(1, n // 10))] = 0.0
+            s[rng.integers(0, n, max(1, n // 10))] = -0.0
+        s32 = s.astype(np.float32)
+        got = _topk_gpu(B, s32, [n], [k], tail)
+        ref = oracle.select_topk(s32, [n], [k], tail)[0]
+        assert np.array_equal(got, ref), variant
+
+
+def test_topk_ragged_batch(B, oracle):
+    rng = np.random.default_rng(77)
+    lens = [5000, 0, 33, 12289, 4096, 1]
+    ks = [250, 0, 1, 600, 4000, 0]
+    tail = 0
+    s = rng.standard_normal(sum(lens)).astype(np.float32)
+    s[rng.integers(0, sum(lens), 3000)] = 0.5
+    got = _topk_gpu(B, s, lens, ks, tail)
+    ref = np.concatenate(oracle.select_topk(s, lens, ks, tail))
+    assert np.array_equal(got, ref)
+    lens, ks, tail = [5000, 40, 12289], [250, 3, 600], 32
+    s = rng.standard_normal(sum(lens)).astype(np.float32)
+    got = _topk_gpu(B, s, lens, ks, tail)
+    ref = np.concatenate(oracle.select_topk(s, lens, ks, tail))
+    assert np.array_equal(got, ref)
+
+
+# ------------------------------------------------------------------ gather (Alg. 1 line 17)
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64), (torch.bfloat16, 72),
+                                     (torch.bfloat16, 3)])
+def test_gather_bit_exact(B, oracle, dtype, d):
+    rng = np.random.default_rng(9)
+    G = 3
+    lens = [100, 7, 300]
+    rows = [10, 7, 33]
+    total = sum(lens)
+    k = torch.randn(G, total, d, device="cuda").to(dtype)
+    v = torch.randn(G, total, d, device="cuda").to(dtype)
+    idx_list = [np.sort(rng.choice(n, r, replace=False)).astype(np.int32) for n, r in zip(lens, rows)]
+    idx = torch.tensor(np.concatenate(idx_list), device="cuda")
+    cu = [0, 100, 107, 407]
+    kd = torch.zeros(G, sum(rows), d, dtype=dtype, device="cuda")
+    vd = torch.zeros_like(kd)
+    B.structkv_gather_kv(k, v, kd, vd, cu, rows, idx)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_oracle_array(kd), oracle.gather_kv(to_oracle_array(k), idx_list, lens))
+    assert np.array_equal(to_oracle_array(vd), oracle.gather_kv(to_oracle_array(v), idx_list, lens))
+    # identity gather, K only
+    ident = torch.arange(total, dtype=torch.int32, device="cuda")
+    ident_local = torch.cat([torch.arange(n, dtype=torch.int32) for n in lens]).cuda()
+    kd2 = torch.zeros_like(k)
+    B.structkv_gather_kv(k, None, kd2, None, cu, lens, ident_local)
+    torch.cuda.synchronize()
+    assert torch.equal(kd2, k) and ident.numel() == total
+
+
+def test_gather_strided_and_offset_views(B, oracle):
+    # token-major source, destination with padding between rows, both at odd element offsets
+    G, n, d, r = 2, 50, 128, 9
+    base = torch.randn(n, G, d + 8, device="cuda").to(torch.bfloat16)
+    src = base[:, :, 3:3 + d].permute(1, 0, 2)              # [G, n, d], misaligned by 6 bytes
+    dbase = torch.zeros(G, r, d + 2, dtype=torch.bfloat16, device="cuda")
+    dst = dbase[:, :, 1:1 + d]
+    idx_np = np.array([0, 5, 6, 7, 20, 33, 41, 48, 49], np.int32)
+    B.structkv_gather_kv(src, None, dst, None, [0, n], [r], torch.tensor(idx_np, device="cuda"))
+    torch.cuda.synchronize()
+    ref = oracle.gather_kv(to_oracle_array(src.contiguous()), [idx_np], [n])
+    assert np.array_equal(to_oracle_array(dst.contiguous()), ref)
+    assert torch.all(dbase[:, :, 0] == 0) and torch.all(dbase[:, :, -1] == 0)
+
+
+def test_gather_out_of_range_index_is_contained(B):
+    G, n, d = 1, 10, 128
+    k = torch.randn(G, n, d, device="cuda").to(torch.bfloat16)
+    kd = torch.zeros(G, 3, d, dtype=torch.bfloat16, device="cuda")
+    B.structkv_gather_kv(k, None, kd, None, [0, n], [3], torch.tensor([2, 10, -1], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(kd[0, 0], k[0, 2]) and torch.equal(kd[0, 1], k[0, 0]) and torch.equal(kd[0, 2], k[0, 0])
+
+
+# ------------------------------------------------------------------ whole sweeps
+
+def test_tiny_config_full_sweep(sweep_mod, oracle):
+    wl = workloads.C1_TINY
+    sw, C = sweep_against_oracle(sweep_mod, oracle, wl, range(wl.n_layers), check_dormant=True)
+    sw.select_struct()
+    torch.cuda.synchronize()
+    got = sw.idx_struct.cpu().numpy()[:sw.rows]
+    same = np.concatenate(oracle.select_topk(sw.centrality.cpu().numpy(), wl.seq_lens, wl.k_per_seq, wl.window))
+    assert np.array_equal(got, same)
+    assert set(workloads.hub_positions(wl)[0]) <= set(got.tolist())     # planted hubs are kept by C
+
+
+@pytest.mark.parametrize("name", ["s_bf16_gqa4", "s_bf16_ragged", "s_f32_ragged"])
+def test_small_sweeps(sweep_mod, oracle, name):
+    wl = workloads.WORKLOADS[name]
+    sweep_against_oracle(sweep_mod, oracle, wl, range(wl.n_layers), check_dormant=True)
