@@ -89,6 +89,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   size_t off = 0;
   p->off_stats = off;   off += align_up(sizeof(float) * GRC * (size_t)p->n_chunks * p->WK * 3 * p->RPC, 256);
   p->off_lse = off;     off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads * s.window, 256);
+  p->off_rowent = off;  off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads * s.window, 256);
   p->off_colsum = off;  off += align_up(sizeof(float) * GRC * (size_t)total, 256);
   p->off_enthead = off; off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads, 256);
   p->total_bytes = off;
@@ -127,17 +128,18 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   float* stats = (float*)(w8 + p.off_stats);
   float* lse2 = (float*)(w8 + p.off_lse);
   float* colsum = (float*)(w8 + p.off_colsum);
+  float* row_ent = (float*)(w8 + p.off_rowent);
   float* ent_head = ent_head_out ? ent_head_out : (float*)(w8 + p.off_enthead);
   const float scale = s.scale > 0.f ? s.scale : 1.0f / std::sqrt((float)s.head_dim);
   const float c2 = (float)((double)scale * 1.4426950408889634);
   auto pass = p.path == 0 ? launch_score_mfma : launch_score_simt;
   if (step_mask & 1)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, nullptr, 1, st));
-  if (step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, ent_head, st));
+  if (step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, st));
   if (step_mask & 4)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, probs, 2, st));
   if (step_mask & 8)
-    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, ent_head, entropy, st));
+    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, st));
   return STRUCTKV_OK;
 }
 
@@ -331,8 +333,8 @@ structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t
   const uintptr_t ptrs = (uintptr_t)k_src | (uintptr_t)v_src | (uintptr_t)k_dst | (uintptr_t)v_dst;
   if (ptrs & (uintptr_t)(elem_bytes - 1)) return fail(STRUCTKV_ERR_INVALID_ARG, "pointers not aligned to the element size");
   const int64_t e = elem_bytes;
-  if (ceil_div(out * head_dim * e / 2, 1024) >= ((int64_t)1 << 31))
-    return fail(STRUCTKV_ERR_UNSUPPORTED, "too many rows for one launch");
+  if (out * head_dim * e / 2 >= ((int64_t)1 << 31) - 4096)
+    return fail(STRUCTKV_ERR_UNSUPPORTED, "too many rows for one launch (rows*head_dim*elem_bytes/2 must stay below 2^31)");
   SKV_HIP_CHECK(launch_gather(k_src, v_src, src_stride_head * e, src_stride_tok * e, k_dst, v_dst,
                               dst_stride_head * e, dst_stride_tok * e, n_kv_heads, head_dim * elem_bytes, seq,
                               idx, (hipStream_t)stream));

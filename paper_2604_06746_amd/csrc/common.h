@@ -44,7 +44,7 @@ struct ScorePlan {
   int RB, WR;        // MFMA path: 32-row blocks per wave, waves along rows
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
   // workspace carve (byte offsets)
-  size_t off_stats, off_lse, off_colsum, off_enthead, total_bytes;
+  size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;
 };
 
 // Launchers (each enqueues on `stream`, returns hipGetLastError()).
@@ -57,10 +57,10 @@ hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const 
                              float* stats, const float* lse2, float* colsum, int64_t total,
                              float* probs, int pass, hipStream_t st);
 hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                                const float* stats, float* lse2, float* ent_head, hipStream_t st);
+                                const float* stats, float* lse2, float* row_ent, hipStream_t st);
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                               const float* colsum, int64_t total, float* indeg,
-                               const float* ent_head, float* entropy, hipStream_t st);
+                               const float* colsum, int64_t total, float* indeg, const float* row_ent,
+                               float* ent_head, float* entropy, hipStream_t st);
 hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st);
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);

@@ -10,31 +10,31 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
-template <typename V>
+template <typename V, bool POW2>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     const uint8_t* __restrict__ src0, const uint8_t* __restrict__ src1, uint8_t* __restrict__ dst0,
-    uint8_t* __restrict__ dst1, int64_t ssh, int64_t sst, int64_t dsh, int64_t dst_tok, int units_per_row,
-    int64_t total_units, SeqTable seq, const int32_t* __restrict__ idx) {
+    uint8_t* __restrict__ dst1, int64_t ssh, int64_t sst, int64_t dsh, int64_t dst_tok, uint32_t units_per_row,
+    uint32_t upr_shift, uint32_t total_units, SeqTable seq, const int32_t* __restrict__ idx) {
   const int g = blockIdx.y;
   const uint8_t* src = (blockIdx.z == 0 ? src0 : src1) + (int64_t)g * ssh;
   uint8_t* dst = (blockIdx.z == 0 ? dst0 : dst1) + (int64_t)g * dsh;
-  const int64_t base = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  const uint32_t base = blockIdx.x * (uint32_t)(kThreads * kUnroll) + threadIdx.x;
   V val[kUnroll];
   int64_t doff[kUnroll];
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i) {
-    const int64_t lin = base + (int64_t)i * kThreads;
+    const uint32_t lin = base + (uint32_t)i * kThreads;
     doff[i] = -1;
     if (lin < total_units) {
-      const int64_t row = lin / units_per_row;
-      const int u = (int)(lin - row * units_per_row);
+      const uint32_t row = POW2 ? lin >> upr_shift : lin / units_per_row;
+      const uint32_t u = lin - row * units_per_row;
       int b = 0;
-      for (int bb = 1; bb < seq.batch; ++bb) b += row >= seq.out_off[bb];
+      for (int bb = 1; bb < seq.batch; ++bb) b += (int64_t)row >= seq.out_off[bb];
       const int64_t n = seq.cu[b + 1] - seq.cu[b];
       int64_t j = idx[row];
       if (j < 0 || j >= n) j = 0;
       val[i] = *reinterpret_cast<const V*>(src + (seq.cu[b] + j) * sst + (int64_t)u * sizeof(V));
-      doff[i] = row * dst_tok + (int64_t)u * sizeof(V);
+      doff[i] = (int64_t)row * dst_tok + (int64_t)u * sizeof(V);
     }
   }
 #pragma unroll
@@ -64,16 +64,18 @@ hipError_t launch_gather(const void* k_src, const void* v_src, int64_t ssh, int6
   const int vec = (bits & 15) == 0 ? 16 : ((bits & 3) == 0 ? 4 : 2);
   const int upr = row_bytes / vec;
   const int64_t total_units = rows * upr;
+  if (total_units >= ((int64_t)1 << 31) - kThreads * kUnroll) return hipErrorInvalidValue;  // host checks this first
+  const bool pow2 = (upr & (upr - 1)) == 0;
+  uint32_t sh = 0;
+  while ((1 << sh) < upr) ++sh;
   dim3 grid((unsigned)ceil_div(total_units, kThreads * kUnroll), (unsigned)G, (unsigned)nz), blk(kThreads);
-  if (vec == 16)
-    hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh, dst_tok,
-                       upr, total_units, seq, idx);
-  else if (vec == 4)
-    hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh,
-                       dst_tok, upr, total_units, seq, idx);
-  else
-    hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh,
-                       dst_tok, upr, total_units, seq, idx);
+#define SKV_GATHER(V, P)                                                                              \
+  hipLaunchKernelGGL((gather_rows_kernel<V, P>), grid, blk, 0, st, s0, s1, d0, d1, ssh, sst, dsh, dst_tok, \
+                     (uint32_t)upr, sh, (uint32_t)total_units, seq, idx)
+  if (vec == 16) { if (pow2) SKV_GATHER(uint4, true); else SKV_GATHER(uint4, false); }
+  else if (vec == 4) { if (pow2) SKV_GATHER(uint32_t, true); else SKV_GATHER(uint32_t, false); }
+  else { if (pow2) SKV_GATHER(uint16_t, true); else SKV_GATHER(uint16_t, false); }
+#undef SKV_GATHER
   return hipGetLastError();
 }
 

@@ -1,9 +1,8 @@
 // Small kernels around the two scoring passes:
 //   combine : merge the per-key-chunk softmax statistics of every query row into
-//             lse2 = M + log2 Z (what pass 2 normalises with) and the row entropies of Eq. 4,
-//             averaged over the window rows of each head.
+//             lse2 = M + log2 Z (what pass 2 normalises with) and the row entropies of Eq. 4.
 //   reduce  : D_j = sum over KV heads / row-chunks of the pass-2 column sums (Eq. 2 without 1/w),
-//             plus the mean over heads that finishes Eq. 4.
+//             plus the means over window rows and heads that finish Eq. 4.
 //   accumulate : C <- lambda C + inv_w D   (Alg. 1 line 6 / Eq. 3).
 #include "common.h"
 
@@ -12,50 +11,60 @@ namespace {
 
 constexpr float kLn2 = 0.6931471805599453f;
 
-// one workgroup per (sequence b, KV head g); thread <-> query row of the group
+// merge (M, Z, E) of two disjoint key sets, log2 domain: Z = sum 2^(x-M), E = sum 2^(x-M)(x-M)
+__device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float Z2, float E2) {
+  const float Mn = fmaxf(M, M2);
+  const float d1 = M - Mn, d2 = M2 - Mn;
+  const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
+  E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
+  Z = Z * f1 + Z2 * f2;
+  M = Mn;
+}
+
+// one workgroup per (sequence b, KV head g, block of 32 query rows); 8 threads share a row and split
+// its partial statistics, then merge in a fixed tree
 __global__ __launch_bounds__(256) void score_combine_kernel(
-    SeqTable seq, int Hq, int G, int w, int R, int RPC, int RC, int WK, int64_t n_chunks,
-    const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ ent_head) {
-  extern __shared__ float row_ent[];  // [R]
-  const int b = blockIdx.x / G, g = blockIdx.x % G;
+    SeqTable seq, int G, int R, int RPC, int RC, int WK, int64_t n_chunks, int row_blocks,
+    const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ row_ent) {
+  const int rblk = blockIdx.x % row_blocks;
+  const int bg = blockIdx.x / row_blocks;
+  const int b = bg / G, g = bg % G;
+  const int row = rblk * 32 + (threadIdx.x >> 3);
+  const int cl = threadIdx.x & 7;
   const int64_t c0 = seq.chunk_start[b], c1 = seq.chunk_start[b + 1];
-  const int gs = Hq / G;
-  for (int row = threadIdx.x; row < R; row += blockDim.x) {
-    const int rc = row / RPC, rr = row % RPC;
-    const int grc = g * RC + rc;
-    float M = -1.0e30f, Z = 0.f, E = 0.f;
-    for (int64_t c = c0; c < c1; ++c) {
-      for (int wk = 0; wk < WK; ++wk) {
-        const float* sp = stats + ((((int64_t)grc * n_chunks + c) * WK + wk) * 3) * RPC + rr;
-        const float M2 = sp[0], Z2 = sp[RPC], E2 = sp[2 * RPC];
-        const float Mn = fmaxf(M, M2);
-        const float d1 = M - Mn, d2 = M2 - Mn;
-        const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
-        E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
-        Z = Z * f1 + Z2 * f2;
-        M = Mn;
-      }
-    }
+  const int rowc = min(row, R - 1);
+  const int rc = rowc / RPC, rr = rowc % RPC;
+  const int grc = g * RC + rc;
+  float M = -1.0e30f, Z = 0.f, E = 0.f;
+  const int64_t np = (c1 - c0) * WK;
+  const float* base = stats + (((int64_t)grc * n_chunks + c0) * WK * 3) * RPC + rr;
+  for (int64_t p = cl; p < np; p += 8) {
+    const float* sp = base + p * 3 * RPC;
+    merge_stats(M, Z, E, sp[0], sp[RPC], sp[2 * RPC]);
+  }
+  for (int off = 1; off < 8; off <<= 1) {
+    const float M2 = __shfl_xor(M, off), Z2 = __shfl_xor(Z, off), E2 = __shfl_xor(E, off);
+    merge_stats(M, Z, E, M2, Z2, E2);
+  }
+  if (cl == 0 && row < R) {
     float ent = 0.f, l2 = 0.f;
     if (c1 > c0) {
       const float lz = __log2f(Z);
       l2 = M + lz;
       ent = kLn2 * (lz - E / Z);   // -sum a ln a  with a = 2^(x-M)/Z
     }
-    lse2[(int64_t)b * G * R + (int64_t)g * R + row] = l2;
-    row_ent[row] = ent;
-  }
-  __syncthreads();
-  for (int hl = threadIdx.x; hl < gs; hl += blockDim.x) {
-    float s = 0.f;
-    for (int i = 0; i < w; ++i) s += row_ent[hl * w + i];
-    ent_head[(int64_t)b * Hq + g * gs + hl] = s / (float)w;
+    const int64_t o = (int64_t)b * G * R + (int64_t)g * R + row;
+    lse2[o] = l2;
+    row_ent[o] = ent;
   }
 }
 
+// grid covers the tokens in float4 units; workgroups b < B also finish Eq. 4 for sequence b
 __global__ __launch_bounds__(256) void score_reduce_kernel(
     const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
-    const float* __restrict__ ent_head, float* __restrict__ entropy, int B, int Hq, int vec) {
+    const float* __restrict__ row_ent, float* __restrict__ ent_head, float* __restrict__ entropy, int B,
+    int Hq, int w, int vec) {
+  __shared__ float hsum[256];
   const int64_t i4 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (vec && i4 + 3 < total) {
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -71,12 +80,24 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
       indeg[i] = a;
     }
   }
-  if (threadIdx.x == 0) {
-    for (int b = blockIdx.x; b < B; b += gridDim.x) {
+  for (int b = blockIdx.x; b < B; b += gridDim.x) {   // uniform per workgroup
+    float part = 0.f;
+    for (int h = threadIdx.x; h < Hq; h += blockDim.x) {
+      const float* re = row_ent + ((int64_t)b * Hq + h) * w;
       float s = 0.f;
-      for (int h = 0; h < Hq; ++h) s += ent_head[(int64_t)b * Hq + h];
+      for (int i = 0; i < w; ++i) s += re[i];
+      s /= (float)w;
+      ent_head[(int64_t)b * Hq + h] = s;
+      part += s;
+    }
+    hsum[threadIdx.x] = part;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float s = 0.f;
+      for (int t = 0; t < 256; ++t) s += hsum[t];
       entropy[b] = s / (float)Hq;
     }
+    __syncthreads();
   }
 }
 
@@ -104,23 +125,24 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, 
 }  // namespace
 
 hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                                const float* stats, float* lse2, float* ent_head, hipStream_t st) {
-  const int blocks = seq.batch * s.n_kv_heads;
+                                const float* stats, float* lse2, float* row_ent, hipStream_t st) {
+  const int row_blocks = (int)ceil_div(p.R, 32);
+  const int64_t blocks = (int64_t)seq.batch * s.n_kv_heads * row_blocks;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(score_combine_kernel, dim3(blocks), dim3(256), sizeof(float) * p.R, st, seq,
-                     s.n_q_heads, s.n_kv_heads, s.window, p.R, p.RPC, p.RC, p.WK, p.n_chunks, stats, lse2,
-                     ent_head);
+  hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, st, seq, s.n_kv_heads, p.R,
+                     p.RPC, p.RC, p.WK, p.n_chunks, row_blocks, stats, lse2, row_ent);
   return hipGetLastError();
 }
 
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                               const float* colsum, int64_t total, float* indeg, const float* ent_head,
-                               float* entropy, hipStream_t st) {
+                               const float* colsum, int64_t total, float* indeg, const float* row_ent,
+                               float* ent_head, float* entropy, hipStream_t st) {
   int64_t blocks = ceil_div(ceil_div(total, 4), 256);
   if (blocks == 0) blocks = 1;
   const int vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum) & 15) == 0;
   hipLaunchKernelGGL(score_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                     s.n_kv_heads * p.RC, total, indeg, ent_head, entropy, seq.batch, s.n_q_heads, vec);
+                     s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
+                     s.window, vec);
   return hipGetLastError();
 }
 

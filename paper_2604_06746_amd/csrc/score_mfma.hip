@@ -12,6 +12,8 @@
 // The scale is applied in fp32 after the MFMA (Q is never re-rounded).
 #include "common.h"
 
+#include <type_traits>
+
 namespace skv {
 namespace {
 
@@ -41,6 +43,7 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
 
   __shared__ __attribute__((aligned(16))) uint8_t kbuf[2][TK * PITCH];
   __shared__ float cs_lds[PASS == 2 ? 2 : 1][WR][TK];
+  __shared__ __attribute__((aligned(16))) float nl_lds[PASS == 2 ? RPC : 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -67,145 +70,168 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
   for (int rb = 0; rb < RB; ++rb) {
     const int grow = min(rc * RPC + (wr * RB + rb) * 32 + l32, R - 1);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int ks = 0; ks < KS; ++ks) {
       qf[rb][ks] = *reinterpret_cast<const bf16x8*>(qg + (int64_t)grow * D + ks * 16 + 8 * lh);
+      // opaque to the compiler from here on: otherwise it re-loads the operands from global memory
+      // inside the key loop instead of keeping them in registers
+      asm volatile("" : "+v"(qf[rb][ks]));
+    }
   }
 
   const uint16_t* kg = k + (int64_t)g * ksh + tok0 * kst;
-  u32x4 stage[NP];
-  auto load_tile = [&](int64_t t0) {
+  // two K tiles are kept in flight in registers (about two tile-times of HBM latency hidden)
+  u32x4 stage[2][NP];
+  auto load_tile = [&](auto slot_tag, int64_t t0) {
+    constexpr int SLOT = decltype(slot_tag)::value;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int p = tid + 256 * i;
       const int key = p / SEGS, seg = p % SEGS;
       const int64_t j = min(t0 + key, n - 1);
-      stage[i] = *reinterpret_cast<const u32x4*>(kg + j * kst + seg * 8);
+      stage[SLOT][i] = *reinterpret_cast<const u32x4*>(kg + j * kst + seg * 8);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](auto slot_tag, int buf) {
+    constexpr int SLOT = decltype(slot_tag)::value;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int p = tid + 256 * i;
       const int key = p / SEGS, seg = p % SEGS;
-      *reinterpret_cast<u32x4*>(&kbuf[buf][key * PITCH + seg * 16]) = stage[i];
+      *reinterpret_cast<u32x4*>(&kbuf[buf][key * PITCH + seg * 16]) = stage[SLOT][i];
     }
   };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
 
   // pass-1 state: this lane's query row(s)
   float M[RB], Z[RB], E[RB];
-  int lim1[RB];  // causal visibility limit of this lane's row (pass 1)
-  // pass-2 state: -lse2 of the 16 rows this lane sees per row block
-  float nl[RB][16];
+  int lim1[RB];   // window index of this lane's row (pass 1, causal limit)
   int rbase[RB];  // first of the 16 rows this lane sees in a row block (pass 2): row = rbase + 8*(i/4) + i%4
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     M[rb] = kNegBig; Z[rb] = 0.f; E[rb] = 0.f;
-    const int grow = rc * RPC + (wr * RB + rb) * 32 + l32;
-    lim1[rb] = 0;
+    lim1[rb] = (rc * RPC + (wr * RB + rb) * 32 + l32) % w;
     rbase[rb] = rc * RPC + (wr * RB + rb) * 32 + 4 * lh;
-    if (PASS == 1) lim1[rb] = grow % w;
-    if (PASS == 2) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int r2 = rc * RPC + (wr * RB + rb) * 32 + 8 * (i / 4) + 4 * lh + (i % 4);
-        nl[rb][i] = r2 < R ? -lse2[(int64_t)b * G * R + (int64_t)g * R + r2] : -INFINITY;
-      }
+  }
+  if (PASS == 2) {
+    // -lse2 of the row-chunk's rows (padded rows get -inf so that they contribute exactly 0)
+    for (int r = tid; r < RPC; r += 256) {
+      const int r2 = rc * RPC + r;
+      nl_lds[r] = r2 < R ? -lse2[(int64_t)b * G * R + (int64_t)g * R + r2] : -INFINITY;
     }
   }
 
-  if (ntiles > 0) {
-    load_tile(key0);
-    store_tile(0);
-  }
+  if (ntiles > 0) load_tile(S0{}, key0);
+  if (ntiles > 1) load_tile(S1{}, key0 + TK);
+  if (ntiles > 0) store_tile(S0{}, 0);
   __syncthreads();
 
-  for (int it = 0; it < ntiles; ++it) {
-    const int64_t t0 = key0 + (int64_t)it * TK;
-    const int buf = it & 1;
-    if (it + 1 < ntiles) load_tile(t0 + TK);
-    const bool masked = t0 + TK > n_full;
-
+  // one 32-key sub-tile: MFMA, then the softmax work; MASKED is a compile-time switch so that full
+  // tiles carry no masking instructions at all
+  auto sub_tile = [&](auto masked_tag, int buf, int sub, int t0i) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    floatx16 acc[RB];
 #pragma unroll
-    for (int sp = 0; sp < SPW; ++sp) {
-      const int sub = WK == 1 ? sp : wk;
-      floatx16 acc[RB];
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
+      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
+          &kbuf[buf][(sub * 32 + l32) * PITCH + ks * 32 + 16 * lh]);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
-            &kbuf[buf][(sub * 32 + l32) * PITCH + ks * 32 + 16 * lh]);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          if (PASS == 1) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0);
-          else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, acc[rb], 0, 0, 0);
-        }
+      for (int rb = 0; rb < RB; ++rb) {
+        if (PASS == 1) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0);
+        else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, acc[rb], 0, 0, 0);
       }
-
-      if (PASS == 1) {
+    }
+    const int ni = (int)n;
+    if (PASS == 1) {
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          if (masked) {
-            const int64_t lim = causal ? n - w + lim1[rb] + 1 : n;
+      for (int rb = 0; rb < RB; ++rb) {
+        if (MASKED) {
+          const int lim = causal ? ni - w + lim1[rb] + 1 : ni;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int64_t j = t0 + sub * 32 + 8 * (i / 4) + 4 * lh + (i % 4);
-              if (j >= lim) acc[rb][i] = -INFINITY;
-            }
+          for (int i = 0; i < 16; ++i) {
+            const int j = t0i + sub * 32 + 8 * (i / 4) + 4 * lh + (i % 4);
+            if (j >= lim) acc[rb][i] = -INFINITY;
           }
-          float tm = fmaxf(acc[rb][0], acc[rb][1]);
-#pragma unroll
-          for (int i = 2; i < 16; i += 2) tm = fmaxf(tm, fmaxf(acc[rb][i], acc[rb][i + 1]));
-          const float Mn = fmaxf(M[rb], tm * c2);
-          const float dl = M[rb] - Mn;
-          const float f = __builtin_amdgcn_exp2f(dl);
-          float z0 = Z[rb] * f, z1 = 0.f;
-          float e0 = (E[rb] + dl * Z[rb]) * f, e1 = 0.f;
-          const float nm = -Mn;
-#pragma unroll
-          for (int i = 0; i < 16; i += 2) {
-            float ta = fmaf(acc[rb][i], c2, nm);
-            float tb = fmaf(acc[rb][i + 1], c2, nm);
-            if (masked) { ta = fmaxf(ta, -200.f); tb = fmaxf(tb, -200.f); }
-            const float pa = __builtin_amdgcn_exp2f(ta);
-            const float pb = __builtin_amdgcn_exp2f(tb);
-            z0 += pa; z1 += pb;
-            e0 = fmaf(pa, ta, e0); e1 = fmaf(pb, tb, e1);
-          }
-          M[rb] = Mn; Z[rb] = z0 + z1; E[rb] = e0 + e1;
         }
-      } else {
-        const int64_t j = t0 + sub * 32 + l32;   // this lane's key
-        float c0 = 0.f, c1 = 0.f;
+        float tm = fmaxf(fmaxf(acc[rb][0], acc[rb][1]), acc[rb][2]);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+        for (int i = 3; i < 15; i += 2) tm = fmaxf(fmaxf(tm, acc[rb][i]), acc[rb][i + 1]);
+        tm = fmaxf(tm, acc[rb][15]);
+        const float Mn = fmaxf(M[rb], tm * c2);
+        const float dl = M[rb] - Mn;
+        const float f = __builtin_amdgcn_exp2f(dl);
+        float z0 = Z[rb] * f, z1 = 0.f;
+        float e0 = (E[rb] + dl * Z[rb]) * f, e1 = 0.f;
+        const float nm = -Mn;
 #pragma unroll
-          for (int i = 0; i < 16; i += 2) {
-            float pa = __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nl[rb][i]));
-            float pb = __builtin_amdgcn_exp2f(fmaf(acc[rb][i + 1], c2, nl[rb][i + 1]));
-            const int ra = rbase[rb] + 8 * (i / 4) + (i % 4), rbw = ra + 1;
-            if (masked) {
-              const int64_t la = causal ? n - w + (ra % w) + 1 : n;
-              const int64_t lb = causal ? n - w + (rbw % w) + 1 : n;
+        for (int i = 0; i < 16; i += 2) {
+          float ta = fmaf(acc[rb][i], c2, nm);
+          float tb = fmaf(acc[rb][i + 1], c2, nm);
+          if (MASKED) { ta = fmaxf(ta, -200.f); tb = fmaxf(tb, -200.f); }   // 2^-200 = 0, and 0 * -200 = 0
+          const float pa = __builtin_amdgcn_exp2f(ta);
+          const float pb = __builtin_amdgcn_exp2f(tb);
+          z0 += pa; z1 += pb;
+          e0 = fmaf(pa, ta, e0); e1 = fmaf(pb, tb, e1);
+        }
+        M[rb] = Mn; Z[rb] = z0 + z1; E[rb] = e0 + e1;
+      }
+    } else {
+      const int j = t0i + sub * 32 + l32;   // this lane's key
+      float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const float4 nl4 = *reinterpret_cast<const float4*>(&nl_lds[(wr * RB + rb) * 32 + 8 * q4 + 4 * lh]);
+          const float nlv[4] = {nl4.x, nl4.y, nl4.z, nl4.w};
+#pragma unroll
+          for (int e = 0; e < 4; e += 2) {
+            const int i = 4 * q4 + e;
+            float pa = __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nlv[e]));
+            float pb = __builtin_amdgcn_exp2f(fmaf(acc[rb][i + 1], c2, nlv[e + 1]));
+            const int ra = rbase[rb] + 8 * q4 + e, rbw = ra + 1;
+            if (MASKED) {
+              const int la = causal ? ni - w + (ra % w) + 1 : ni;
+              const int lb = causal ? ni - w + (rbw % w) + 1 : ni;
               if (j >= la) pa = 0.f;
               if (j >= lb) pb = 0.f;
             }
-            if (DUMP && j < key_end) {
+            if (DUMP && j < ni) {
               if (ra < R) probs[((int64_t)g * R + ra) * n + j] = pa;
               if (rbw < R) probs[((int64_t)g * R + rbw) * n + j] = pb;
             }
             c0 += pa; c1 += pb;
           }
         }
-        float cs = c0 + c1;
-        cs += __shfl_xor(cs, 32);
-        if (lh == 0) cs_lds[PASS == 2 ? buf : 0][wr][sub * 32 + l32] = cs;
       }
+      float cs = c0 + c1;
+      cs += __shfl_xor(cs, 32);
+      if (lh == 0) cs_lds[PASS == 2 ? buf : 0][wr][sub * 32 + l32] = cs;
     }
+  };
 
-    if (it + 1 < ntiles) store_tile(buf ^ 1);
+  // tile `it` sits in LDS buffer it&1; its register slot (it&1) is free again and takes tile it+2
+  auto tile_step = [&](auto slot_tag, int it) {
+    using SLOT = decltype(slot_tag);
+    using OTHER = std::integral_constant<int, 1 - SLOT::value>;
+    const int64_t t0 = key0 + (int64_t)it * TK;
+    const int buf = SLOT::value;
+    if (it + 2 < ntiles) load_tile(SLOT{}, t0 + 2 * TK);
+    const bool masked = t0 + TK > n_full;
+    if (!masked) {
+#pragma unroll
+      for (int sp = 0; sp < SPW; ++sp)
+        sub_tile(std::integral_constant<bool, false>{}, buf, WK == 1 ? sp : wk, (int)t0);
+    } else {
+#pragma unroll
+      for (int sp = 0; sp < SPW; ++sp)
+        sub_tile(std::integral_constant<bool, true>{}, buf, WK == 1 ? sp : wk, (int)t0);
+    }
+    if (it + 1 < ntiles) store_tile(OTHER{}, buf ^ 1);
     __syncthreads();
     if (PASS == 2) {
       if (tid < TK && t0 + tid < key_end) {
@@ -215,6 +241,10 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
         colsum[(int64_t)grc * total + tok0 + t0 + tid] = s;
       }
     }
+  };
+  for (int it = 0; it < ntiles; it += 2) {
+    tile_step(S0{}, it);
+    if (it + 1 < ntiles) tile_step(S1{}, it + 1);
   }
 
   if (PASS == 1) {
