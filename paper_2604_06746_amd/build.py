@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstructkv.so")
-SOURCES = ["api.cpp", "score_mfma.hip", "score_simt.hip", "score_combine.hip", "topk.hip", "gather.hip"]
+SOURCES = ["api.cpp", "score_mfma_ring.hip", "score_simt.hip", "score_combine.hip", "topk.hip", "gather.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-x", "hip",
          # packed-fp32 instruction selection is switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -19,7 +19,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-x", "hip",
 
 # Per-file extras.  The MFMA scoring kernels assume finite inputs (documented in the header): without NaN
 # handling the compiler drops the canonicalising v_max it otherwise puts in front of every fmaxf operand.
-EXTRA = {"score_mfma.hip": ["-fno-honor-nans"]}
+EXTRA = {"score_mfma_ring.hip": ["-fno-honor-nans"]}
 
 
 def _compile(src: str) -> str:

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 namespace skv {
@@ -66,16 +67,24 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->R = gs * s.window;
   p->path = mfma_ok ? 0 : 1;
   if (p->path == 0) {
-    if (p->R > 128) { p->RPC = 256; p->RB = 2; p->WR = 4; p->WK = 1; }
-    else if (p->R > 64) { p->RPC = 128; p->RB = 1; p->WR = 4; p->WK = 1; }
-    else { p->RPC = 64; p->RB = 1; p->WR = 2; p->WK = 2; }
+    // MFMA kernels: one wave owns RPC = 32*RB <= 128 rows and KC keys; a KV group with more rows is cut into
+    // RC row-chunks, two per workgroup, whose waves share the key tiles
+    p->RB = p->R > 64 ? 4 : (p->R > 32 ? 2 : 1);
+    p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
-    // keys per workgroup: long chunks amortise the query-operand load; keep >= ~1024 workgroups
-    int kc = 1024;
-    while (kc > 256 && ceil_div(total, kc) * s.n_kv_heads * p->RC < 1024) kc >>= 1;
-    p->KC = kc;
+    // keys per wave: about one full round of waves over the chip (two waves per SIMD) when the problem
+    // allows it, and at least 256 keys so that loading the query operands (RPC*d*2 bytes per wave) stays
+    // small against the K stream
+    int64_t kc = ceil_div(ceil_div(total * s.n_kv_heads * p->RC, 2048), 32) * 32;
+    if (kc < 256) kc = 256;
+    if (kc > 1024) kc = 1024;
+    if (const char* e = getenv("STRUCTKV_DEBUG_KC")) {   // tuning knob: keys per wave, multiple of 32, >= 256
+      const long v = atol(e);
+      if (v >= 256 && v % 32 == 0) kc = v;
+    }
+    p->KC = (int)kc;
   } else {
-    p->RPC = 16; p->RB = 0; p->WR = 0; p->WK = 1;
+    p->RPC = 16; p->RB = 0; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
     p->KC = 256;
   }
@@ -83,7 +92,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     p->n_chunks = 0;
     for (int b = 0; b < batch; ++b) p->n_chunks += ceil_div(seq->cu[b + 1] - seq->cu[b], p->KC);
   } else {
-    p->n_chunks = total / p->KC + batch;
+    p->n_chunks = total / 256 + batch;   // KC is at least 256 on either path
   }
   const size_t GRC = (size_t)s.n_kv_heads * p->RC;
   size_t off = 0;
@@ -99,6 +108,7 @@ bool mfma_eligible(const structkv_shape& s, const void* q, const void* k, int64_
   if (g_force_path.load() == 1) return false;
   if (s.dtype != STRUCTKV_DTYPE_BF16) return false;
   if (s.head_dim != 64 && s.head_dim != 128) return false;
+  if (s.causal && (s.window % 32) != 0) return false;   // the MFMA kernels' causal masks assume whole 32-row blocks per head
   if ((((uintptr_t)q | (uintptr_t)k) & 15) != 0) return false;
   if ((ksh % 8) != 0 || (kst % 8) != 0) return false;
   return true;
@@ -132,7 +142,7 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   float* ent_head = ent_head_out ? ent_head_out : (float*)(w8 + p.off_enthead);
   const float scale = s.scale > 0.f ? s.scale : 1.0f / std::sqrt((float)s.head_dim);
   const float c2 = (float)((double)scale * 1.4426950408889634);
-  auto pass = p.path == 0 ? launch_score_mfma : launch_score_simt;
+  auto pass = p.path == 0 ? launch_score_mfma_ring : launch_score_simt;
   if (step_mask & 1)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, nullptr, 1, st));
   if (step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, st));
@@ -161,9 +171,9 @@ size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int6
   size_t need = topk_workspace_bytes(batch, total_tokens);
   if (shape) {
     if (check_shape(shape) != STRUCTKV_OK) return 0;
-    for (int path = 0; path < 2; ++path) {
+    for (int mfma = 0; mfma < 2; ++mfma) {
       ScorePlan p;
-      make_plan(*shape, nullptr, batch, total_tokens, path == 0, &p);
+      make_plan(*shape, nullptr, batch, total_tokens, mfma == 1, &p);
       if (p.total_bytes > need) need = p.total_bytes;
     }
   }

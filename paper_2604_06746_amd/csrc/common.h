@@ -35,23 +35,23 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // ---- scoring plan: how one structkv_score_layer call is cut into workgroups ----------------
 struct ScorePlan {
-  int path;          // 0 = bf16 MFMA, 1 = SIMT
+  int path;          // 0 = bf16 MFMA kernels, 1 = SIMT kernels
   int R;             // query rows per KV head: (H_q/G) * w
   int RPC;           // rows per row-chunk (a workgroup's share of R)
   int RC;            // row-chunks per KV head
   int KC;            // keys per key-chunk (one workgroup)
   int WK;            // partial statistics written per (row-chunk, key-chunk)
-  int RB, WR;        // MFMA path: 32-row blocks per wave, waves along rows
+  int RB;            // MFMA path: 32-row blocks per wave (1, 2 or 4)
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
   // workspace carve (byte offsets)
   size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;
 };
 
 // Launchers (each enqueues on `stream`, returns hipGetLastError()).
-hipError_t launch_score_mfma(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                             const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
-                             float* stats, const float* lse2, float* colsum, int64_t total,
-                             float* probs, int pass, hipStream_t st);
+hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                                  const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
+                                  float* stats, const float* lse2, float* colsum, int64_t total,
+                                  float* probs, int pass, hipStream_t st);
 hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                              const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
                              float* stats, const float* lse2, float* colsum, int64_t total,

@@ -1,0 +1,391 @@
+// bf16 MFMA scoring kernels for gfx950 (paper Eq. 1, Eq. 2, Eq. 4): register-resident queries, keys
+// streamed HBM -> LDS by direct-to-LDS loads (no staging registers) through a ring of 32-key tiles.
+//
+// What shaped it (measured on MI355X): a ds_read_b128 stream sustains ~64 B/clk per CU, so an MFMA
+// (32 cycles per SIMD) fed from LDS must reuse each 1 KB operand read for at least 4 MFMAs; a single
+// wave cannot keep a SIMD's vector ALU busy (it issues an instruction every ~5-6 cycles, a
+// transcendental every ~20), so two waves per SIMD (<= 256 registers each) are needed; HBM latency
+// needs ~60 KB of unique loads in flight per CU.  Hence:
+//   * a wave owns a row-chunk of up to 128 query rows (4 blocks of 32) as MFMA operands in registers
+//     for the whole kernel, and reads each key operand from LDS ONCE per 32-key tile (4 MFMAs per read);
+//   * a KV group of 256 rows (GQA 4 x window 64) is two row-chunks = the two waves of a workgroup, which
+//     share the LDS tiles, so K crosses HBM -> L2 -> LDS once per pass;
+//   * tiles are fetched with global_load_lds_dwordx4 (16 B per lane, lane L lands at base + 16 L), three
+//     tiles ahead, into an XOR-swizzled layout that makes the operand reads bank-conflict free;
+//   * inside a wave the MFMAs of row block rb+1 are issued under the softmax arithmetic of row block rb.
+//
+//   pass 1:  S^T = K Q^T   a lane owns ONE query row of each row block and 16 keys: running
+//            M = max x, Z = sum 2^(x-M), E = sum 2^(x-M)(x-M) per row, x = c2 (q.k), c2 = scale log2(e)
+//   pass 2:  S = Q K^T     a lane owns ONE key and 16 rows of each row block; -lse2[row]/c2 rides in
+//            one extra MFMA k-step (three bf16 pieces of it against ones on the key side), so
+//            p = 2^(c2 acc) needs no per-row constant in registers; the lane sums its key's column.
+#include "common.h"
+
+#include <type_traits>
+
+namespace skv {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+
+constexpr float kNegBig = -1.0e30f;
+
+template <bool V> using BoolC = std::integral_constant<bool, V>;
+template <int V> using IntC = std::integral_constant<int, V>;
+
+// round-to-nearest-even bf16 bits of a finite float (or of +-inf)
+__device__ inline uint16_t bf16_bits(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ inline float bf16_value(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring
+template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP>
+__global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst,
+    SeqTable seq, int Hq, int G, int w, int causal, float c2, int R, int RC, int KC, int64_t n_chunks,
+    float* __restrict__ stats, const float* __restrict__ lse2, float* __restrict__ colsum,
+    int64_t total, float* __restrict__ probs) {
+  constexpr int KS = D / 16;        // MFMA k-steps over the head dimension
+  constexpr int RPC = 32 * NRB;     // query rows per wave
+  constexpr int SEGS = D / 8;       // 16-byte pieces per key row
+  constexpr int TILE_BYTES = 32 * D * 2;
+  constexpr int NINST = 32 * SEGS / 64;   // wave-wide 1 KB load instructions per tile
+  constexpr int IPW = NINST / NW;          // ... issued by each wave
+  constexpr int PD = NBUF - 1;             // tiles requested ahead of the one being consumed
+  static_assert(NINST % NW == 0, "tile loads split evenly over the waves");
+  __shared__ __attribute__((aligned(1024))) uint8_t ring[NBUF * TILE_BYTES];
+  // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
+  constexpr int VPM = PASS == 1 ? 11 : 6;
+
+  const int lane = threadIdx.x & 63;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  // workgroup -> (KV head g, group of row-chunks, key chunk); wave -> row-chunk inside the group
+  const int wave = threadIdx.x >> 6;
+  const int rcg = (RC + NW - 1) / NW;
+  const int g = blockIdx.x % G;
+  const int64_t t = blockIdx.x / G;
+  // a wave beyond the last row-chunk still helps loading tiles and keeps the barriers matched; it
+  // computes on a valid chunk (the last one) and simply does not write results
+  const int rc_raw = (int)(t % rcg) * NW + wave;
+  const bool live = rc_raw < RC;
+  const int rc = live ? rc_raw : RC - 1;
+  const int64_t chunk = t / rcg;
+  const int grc = g * RC + rc;
+  int b = 0;
+  while (b + 1 < seq.batch && chunk >= seq.chunk_start[b + 1]) ++b;
+  const int64_t tok0 = seq.cu[b];
+  const int64_t n = seq.cu[b + 1] - tok0;
+  const int ni = (int)n;
+  const int key0 = (int)((chunk - seq.chunk_start[b]) * (int64_t)KC);
+  const int key_end = min(ni, key0 + KC);
+  const int n_full = causal ? ni - w : ni;   // keys below n_full are visible to every row
+  const int nsub = (key_end - key0 + 31) / 32;
+
+  // ---- the row-chunk's queries as MFMA operands (registers, whole kernel) ----
+  const uint16_t* qg = q + ((int64_t)b * Hq * w + (int64_t)g * R) * D;
+  bf16x8 qf[NRB][KS];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    const int grow = min(rc * RPC + rb * 32 + l32, R - 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qf[rb][ks] = *reinterpret_cast<const bf16x8*>(qg + (int64_t)grow * D + ks * 16 + 8 * lh);
+  }
+  // opaque to the compiler from here on, so that it keeps the operands in registers instead of re-loading
+  // them inside the key loop (pinned only after ALL loads are in flight: one latency, not one per load)
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rb][ks]));
+
+  // pass 2: the extra k-step.  Query side: -(lse2[row]/c2) in three bf16 pieces (lane half 0, first
+  // three k slots); key side: ones in the same slots.  Padded rows carry -inf, so their p is exactly 0.
+  bf16x8 qaug[PASS == 2 ? NRB : 1] = {};
+  bf16x8 kaug = {};
+  if (PASS == 2) {
+    u16x8 one = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (lh == 0) { one[0] = 0x3F80; one[1] = 0x3F80; one[2] = 0x3F80; }
+    kaug = __builtin_bit_cast(bf16x8, one);
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      const int row = rc * RPC + rb * 32 + l32;
+      u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (lh == 0) {
+        if (row < R) {
+          const float lam = -lse2[(int64_t)b * G * R + (int64_t)g * R + row] / c2;
+          const uint16_t hi = bf16_bits(lam);
+          const float r1 = lam - bf16_value(hi);
+          const uint16_t mid = bf16_bits(r1);
+          const uint16_t lo = bf16_bits(r1 - bf16_value(mid));
+          v[0] = hi; v[1] = mid; v[2] = lo;
+        } else {
+          v[0] = 0xFF80;   // -inf
+        }
+      }
+      qaug[rb] = __builtin_bit_cast(bf16x8, v);
+      asm volatile("" : "+v"(qaug[rb]));
+    }
+  }
+
+  const uint16_t* kg = k + (int64_t)g * ksh + tok0 * kst;
+  // Tile layout in LDS: 16-byte piece (key, seg) sits at unit key*SEGS + (seg ^ swz(key)); any 16
+  // consecutive keys at a fixed seg then hit 16 different groups of 4 banks (conflict-free operand reads).
+  // Loader: instruction I, lane L writes unit I*64 + L, so it must fetch that unit's (key, seg).
+  auto swz = [&](int key) __attribute__((always_inline)) { return SEGS == 16 ? (key & 15) : ((key >> 1) & 7); };
+  // per-lane byte offsets of the units this lane fetches, relative to the tile's first key row
+  uint32_t voff[IPW];
+#pragma unroll
+  for (int ii = 0; ii < IPW; ++ii) {
+    const int unit = (ii * NW + wave) * 64 + lane;
+    const int key = unit / SEGS;
+    voff[ii] = (uint32_t)(key * kst + ((unit % SEGS) ^ swz(key)) * 8) * 2u;
+  }
+  auto issue_tile = [&](int s_idx) __attribute__((always_inline)) {
+    const int jbase = key0 + 32 * s_idx;
+    uint8_t* slot = ring + (s_idx % NBUF) * TILE_BYTES + wave * 1024;
+    const uint8_t* gbase = reinterpret_cast<const uint8_t*>(kg + (int64_t)jbase * kst);   // wave-uniform
+    if (jbase + 32 <= ni) {
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii)
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(gbase + voff[ii]), (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, 0);
+    } else {   // ragged tail: rows past the end re-read the last valid row (their logits are masked)
+#pragma unroll
+      for (int ii = 0; ii < IPW; ++ii) {
+        const int unit = (ii * NW + wave) * 64 + lane;
+        const int key0u = unit / SEGS;
+        const int seg = (unit % SEGS) ^ swz(key0u);
+        const int key = min(key0u, ni - 1 - jbase);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(gbase + (uint32_t)(key * kst + seg * 8) * 2u),
+                                         (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, 0);
+      }
+    }
+  };
+  bf16x8 kf[KS];   // operands of the tile being consumed
+  auto read_tile = [&](int s_idx) __attribute__((always_inline)) {
+    const uint8_t* slot = ring + (s_idx % NBUF) * TILE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int seg = 2 * ks + lh;
+      kf[ks] = *reinterpret_cast<const bf16x8*>(slot + (l32 * SEGS + (seg ^ swz(l32))) * 16);
+    }
+  };
+
+  float M[NRB], Z[NRB], E[NRB];   // pass 1: statistics of this lane's query row in each row block
+  int win[NRB];                   // pass 1: window index of that row (causal limit)
+  int win2[NRB];                  // pass 2: window index of the first of the 16 rows this lane sees
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    M[rb] = kNegBig; Z[rb] = 0.f; E[rb] = 0.f;
+    win[rb] = (rc * RPC + rb * 32 + l32) % w;
+    win2[rb] = (rc * RPC + rb * 32) % w + 4 * lh;
+  }
+  float cs0 = 0.f, cs1 = 0.f;     // pass 2: column sum of this lane's key
+
+  auto mfma_block = [&](floatx16& acc, const bf16x8 (&kf)[KS], auto rb_tag) __attribute__((always_inline)) {
+    constexpr int rb = decltype(rb_tag)::value;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (PASS == 1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], acc, 0, 0, 0);
+      else           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf[ks], acc, 0, 0, 0);
+    }
+    if constexpr (PASS == 2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug[rb], kaug, acc, 0, 0, 0);
+  };
+
+  // softmax arithmetic of one row block against the 32 keys starting at jbase
+  auto softmax_block = [&](auto masked_tag, floatx16& acc, auto rb_tag, int jbase) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    constexpr int rb = decltype(rb_tag)::value;
+    if (PASS == 1) {
+      if (MASKED) {
+        const int lim = causal ? ni - w + win[rb] + 1 : ni;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int j = jbase + 8 * (i / 4) + 4 * lh + (i % 4);
+          if (j >= lim) acc[i] = -INFINITY;
+        }
+      }
+      float tm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+      for (int i = 3; i < 15; i += 2) tm = fmaxf(fmaxf(tm, acc[i]), acc[i + 1]);
+      tm = fmaxf(tm, acc[15]);
+      const float Mn = fmaxf(M[rb], tm * c2);
+      const float dl = M[rb] - Mn;
+      const float f = __builtin_amdgcn_exp2f(dl);
+      float z0 = Z[rb] * f, z1 = 0.f;
+      float e0 = (E[rb] + dl * Z[rb]) * f, e1 = 0.f;
+      const float nm = -Mn;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        float ta = fmaf(acc[i], c2, nm);
+        float tb = fmaf(acc[i + 1], c2, nm);
+        if (MASKED) { ta = fmaxf(ta, -200.f); tb = fmaxf(tb, -200.f); }   // 2^-200 = 0, and 0 * -200 = 0
+        const float pa = __builtin_amdgcn_exp2f(ta);
+        const float pb = __builtin_amdgcn_exp2f(tb);
+        z0 += pa; z1 += pb;
+        e0 = fmaf(pa, ta, e0); e1 = fmaf(pb, tb, e1);
+      }
+      M[rb] = Mn; Z[rb] = z0 + z1; E[rb] = e0 + e1;
+    } else {
+      const int j = jbase + l32;   // this lane's key
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        float pa = __builtin_amdgcn_exp2f(acc[i] * c2);
+        float pb = __builtin_amdgcn_exp2f(acc[i + 1] * c2);
+        const int ra = rc * RPC + rb * 32 + 8 * (i / 4) + 4 * lh + (i % 4), rbw = ra + 1;
+        if (MASKED) {
+          // causal only (keys past the end of the sequence are simply never written), and the window is
+          // a multiple of 32 rows here, so a 32-row block never straddles two heads
+          const int la = ni - w + win2[rb] + 8 * (i / 4) + (i % 4) + 1;
+          if (j >= la) pa = 0.f;
+          if (j >= la + 1) pb = 0.f;
+        }
+        if (DUMP && j < ni) {
+          if (ra < R) probs[((int64_t)g * R + ra) * n + j] = pa;
+          if (rbw < R) probs[((int64_t)g * R + rbw) * n + j] = pb;
+        }
+        cs0 += pa; cs1 += pb;
+      }
+    }
+  };
+
+  auto interleave_hint = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < KS + (PASS == 2 ? 1 : 0); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);   // then a group of vector-ALU instructions
+    }
+  };
+
+  floatx16 acc0, acc1;
+
+  // One tile of 32 keys whose operands are in kf: row block rb+1's MFMAs run under row block rb's softmax.
+  auto sub_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
+    using MT = decltype(masked_tag);
+    mfma_block(acc0, kf, IntC<0>{});
+    auto step = [&](auto rb_tag) __attribute__((always_inline)) {
+      constexpr int rb = decltype(rb_tag)::value;
+      floatx16& mine = (rb & 1) ? acc1 : acc0;
+      floatx16& other = (rb & 1) ? acc0 : acc1;
+      if (rb + 1 < NRB) {
+        mfma_block(other, kf, IntC<(rb + 1 < NRB ? rb + 1 : 0)>{});
+        softmax_block(MT{}, mine, rb_tag, jbase);
+        interleave_hint();
+      } else {
+        softmax_block(MT{}, mine, rb_tag, jbase);
+      }
+    };
+    step(IntC<0>{});
+    if constexpr (NRB > 1) step(IntC<1>{});
+    if constexpr (NRB > 2) { step(IntC<2>{}); step(IntC<3>{}); }
+    if (PASS == 2) {
+      float cs = cs0 + cs1;
+      cs += __shfl_xor(cs, 32);
+      const int j = jbase + l32;
+      if (live && lh == 0 && j < key_end) colsum[(int64_t)grc * total + tok0 + j] = cs;
+      cs0 = 0.f; cs1 = 0.f;
+    }
+  };
+  // prologue: request the first PD tiles
+#pragma unroll
+  for (int i = 0; i < PD; ++i)
+    if (i < nsub) issue_tile(i);
+  for (int s = 0; s < nsub; ++s) {
+    // my share of tile s has landed when at most the later requests (up to PD-1 tiles) are outstanding
+    const int later = min(PD - 1, nsub - 1 - s);
+    if (later >= 3) wait_vmcnt<3 * IPW>();
+    else if (later == 2) wait_vmcnt<2 * IPW>();
+    else if (later == 1) wait_vmcnt<IPW>();
+    else wait_vmcnt<0>();
+    // Plain s_barrier, not __syncthreads(): the fence in the latter waits for ALL outstanding loads, which
+    // would drain the ring.  After the barrier everybody's share of tile s is in LDS (each wave waited for
+    // its own loads above) and everybody is done reading tile s-1's slot.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (s + PD < nsub) issue_tile(s + PD);   // goes into the slot tile s-1 just left
+    read_tile(s);
+    const int jbase = key0 + 32 * s;
+    // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
+    const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
+    if (!masked) sub_tile(BoolC<false>{}, jbase);
+    else         sub_tile(BoolC<true>{}, jbase);
+  }
+
+  if (PASS == 1) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      // the two lane halves hold disjoint key subsets of the same query row
+      const float M2 = __shfl_xor(M[rb], 32), Z2 = __shfl_xor(Z[rb], 32), E2 = __shfl_xor(E[rb], 32);
+      const float Mn = fmaxf(M[rb], M2);
+      const float d1 = M[rb] - Mn, d2 = M2 - Mn;
+      const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
+      const float En = (E[rb] + d1 * Z[rb]) * f1 + (E2 + d2 * Z2) * f2;
+      const float Zn = Z[rb] * f1 + Z2 * f2;
+      if (live && lh == 0) {
+        float* sp = stats + (((int64_t)grc * n_chunks + chunk) * 3) * RPC + rb * 32 + l32;
+        sp[0] = Mn;
+        sp[RPC] = Zn;
+        sp[2 * RPC] = En;
+      }
+    }
+  }
+}
+
+template <int D, int NRB, int NW, int NBUF>
+hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq, const void* q,
+                           const void* k, int64_t ksh, int64_t kst, float c2, float* stats,
+                           const float* lse2, float* colsum, int64_t total, float* probs, int pass,
+                           hipStream_t st) {
+  const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.n_chunks;
+  dim3 g((unsigned)grid), blk(64 * NW);
+#define SKV_ARGS                                                                                        \
+  g, blk, 0, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, seq, s.n_q_heads, s.n_kv_heads,      \
+      s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs
+  if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
+  else if (probs == nullptr) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false>), SKV_ARGS);
+  else hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, true>), SKV_ARGS);
+#undef SKV_ARGS
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
+                                  const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
+                                  float* stats, const float* lse2, float* colsum, int64_t total,
+                                  float* probs, int pass, hipStream_t st) {
+  if (p.n_chunks == 0) return hipSuccess;
+  // two waves (two row-chunks) per workgroup with a 4-tile ring when the KV group has more than 128 rows;
+  // otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
+#define SKV_RING(d, nrb, nw, nbuf)                                                                      \
+  if (s.head_dim == d && p.RB == nrb && (p.RC > 1 ? 2 : 1) == nw)                                       \
+    return launch_ring_cfg<d, nrb, nw, nbuf>(s, p, seq, q, k, ksh, kst, c2, stats, lse2, colsum, total, probs, pass, st)
+  SKV_RING(128, 4, 2, 4);
+  SKV_RING(128, 4, 1, 2);
+  SKV_RING(128, 2, 1, 2);
+  SKV_RING(128, 1, 1, 2);
+  SKV_RING(64, 4, 2, 4);
+  SKV_RING(64, 4, 1, 2);
+  SKV_RING(64, 2, 1, 2);
+  SKV_RING(64, 1, 1, 2);
+#undef SKV_RING
+  return hipErrorInvalidValue;
+}
+
+}  // namespace skv
