@@ -31,7 +31,7 @@ def parse_args():
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the sweep is captured once in a HIP graph and replayed per step")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
-    ap.add_argument("--cpu-sample-layers", type=int, default=8, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample-layers", type=int, default=32, help="layers the CPU oracle is timed on (0 = skip)")
     return ap.parse_args()
 
 

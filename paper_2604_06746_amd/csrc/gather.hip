@@ -8,7 +8,10 @@ namespace skv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
+#ifndef SKV_GATHER_UNROLL
+#define SKV_GATHER_UNROLL 8
+#endif
+constexpr int kUnroll = SKV_GATHER_UNROLL;
 
 template <typename V, bool POW2>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(

@@ -81,20 +81,29 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
     }
   }
   for (int b = blockIdx.x; b < B; b += gridDim.x) {   // uniform per workgroup
+    // eight lanes share a head: each sums every eighth window row, then a fixed shuffle tree
     float part = 0.f;
-    for (int h = threadIdx.x; h < Hq; h += blockDim.x) {
-      const float* re = row_ent + ((int64_t)b * Hq + h) * w;
+    for (int h0 = 0; h0 < Hq; h0 += 32) {
+      const int h = h0 + (threadIdx.x >> 3);
       float s = 0.f;
-      for (int i = 0; i < w; ++i) s += re[i];
-      s /= (float)w;
-      ent_head[(int64_t)b * Hq + h] = s;
-      part += s;
+      if (h < Hq) {
+        const float* re = row_ent + ((int64_t)b * Hq + h) * w;
+        for (int i = threadIdx.x & 7; i < w; i += 8) s += re[i];
+      }
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      if (h < Hq && (threadIdx.x & 7) == 0) {
+        s /= (float)w;
+        ent_head[(int64_t)b * Hq + h] = s;
+        part += s;
+      }
     }
     hsum[threadIdx.x] = part;
     __syncthreads();
     if (threadIdx.x == 0) {
       float s = 0.f;
-      for (int t = 0; t < 256; ++t) s += hsum[t];
+      for (int t = 0; t < 256; t += 8) s += hsum[t];
       entropy[b] = s / (float)Hq;
     }
     __syncthreads();

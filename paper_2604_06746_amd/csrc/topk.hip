@@ -11,7 +11,10 @@
 namespace skv {
 namespace {
 
-constexpr int kChunk = 4096;   // scores per workgroup
+#ifndef SKV_TOPK_CHUNK
+#define SKV_TOPK_CHUNK 4096
+#endif
+constexpr int kChunk = SKV_TOPK_CHUNK;   // scores per workgroup
 constexpr int kThreads = 256;
 constexpr int kPer = kChunk / kThreads;
 constexpr int kBins = 2048;
