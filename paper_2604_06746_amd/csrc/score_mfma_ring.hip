@@ -68,7 +68,7 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
   static_assert(NINST % NW == 0, "tile loads split evenly over the waves");
   __shared__ __attribute__((aligned(1024))) uint8_t ring[NBUF * TILE_BYTES];
   // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
-  constexpr int VPM = PASS == 1 ? 11 : 6;
+  constexpr int VPM = PASS == 1 ? 8 : 4;
 
   const int lane = threadIdx.x & 63;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -269,6 +269,7 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
     for (int i = 0; i < KS + (PASS == 2 ? 1 : 0); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
       __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);   // then a group of vector-ALU instructions
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);     // and two transcendentals (a class of their own)
     }
   };
 
