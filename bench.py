@@ -30,6 +30,8 @@ def parse_args():
     ap.add_argument("--workload", default="c3_llama8b_128k")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the sweep is captured once in a HIP graph and replayed per step")
+    ap.add_argument("--overlap", type=int, default=1,
+                    help="1: selection + gather of layer l run on a side stream under the scoring of layer l+1")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
     ap.add_argument("--cpu-sample-layers", type=int, default=32, help="layers the CPU oracle is timed on (0 = skip)")
     return ap.parse_args()
@@ -57,11 +59,16 @@ def main():
     sw = sweep_mod.LayerSweep(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.torch_dtype,
                               wl.seq_lens, wl.k_per_seq, lam=wl.lam, n_layers_out=L)
 
+    side_stream = torch.cuda.Stream() if args.overlap else None   # default priority
+
     def step():
         sw.reset()
-        for l in range(L):
-            x = layers[l]
-            sw.layer(x.q_win, x.k, x.v, slot=l)
+        if side_stream is not None:
+            sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side_stream)
+        else:
+            for l in range(L):
+                x = layers[l]
+                sw.layer(x.q_win, x.k, x.v, slot=l)
         sw.select_struct()
 
     mode = args.mode
@@ -186,7 +193,7 @@ def main():
         "config": {"workload": wl.name, "layers": L, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_lens": list(wl.seq_lens) if wl.batch > 1 else wl.seq_lens[0],
                    "window": wl.window, "k": list(wl.k_per_seq) if wl.batch > 1 else wl.k_per_seq[0],
-                   "launch": mode},
+                   "launch": mode, "streams": 2 if args.overlap else 1},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     out.update(extra)

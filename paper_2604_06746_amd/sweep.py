@@ -32,7 +32,12 @@ class LayerSweep:
         ws_bytes = B.structkv_workspace_bytes(self.shape, self.batch, self.total)
         dev = torch.device(device)
         self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
-        self.indeg = torch.empty(self.total, dtype=torch.float32, device=dev)
+        # second score vector + a workspace of its own for the selection, used when selection and gather of one
+        # layer run on a side stream while the next layer is being scored (sweep_overlapped)
+        topk_bytes = B.structkv_workspace_bytes(None, self.batch, self.total)
+        self.topk_workspace = torch.empty(max(topk_bytes, 256), dtype=torch.uint8, device=dev)
+        self._indeg2 = [torch.empty(self.total, dtype=torch.float32, device=dev) for _ in range(2)]
+        self.indeg = self._indeg2[0]
         self.centrality = torch.zeros(self.total, dtype=torch.float32, device=dev)
         self.entropy = torch.empty(max(self.batch, 1), dtype=torch.float32, device=dev)
         self.entropy_per_head = torch.empty(max(self.batch, 1), n_q_heads, dtype=torch.float32, device=dev)
@@ -71,3 +76,32 @@ class LayerSweep:
         self.accumulate(stream)
         self.select_kv(stream)
         self.gather(k, v, slot, stream)
+
+    def sweep_overlapped(self, layers, side_stream, slots=None) -> None:
+        """All layers of a prefill: the scoring chain (score -> accumulate) of layer l+1 runs on the current
+        stream while selection and gather of layer l run on `side_stream`.  Same calls and same results as
+        calling layer() in a loop; only the streams differ.  `layers` yields (q_win, k, v); per-layer
+        outputs go to cache slot slots[l] (default l).  Ends with both streams joined on the current one.
+        """
+        main = torch.cuda.current_stream()
+        scored = []      # events: layer l's scores are complete
+        selected = []    # events: layer l's selection has finished reading the score vector
+        for l, (q_win, k, v) in enumerate(layers):
+            self.indeg = self._indeg2[l & 1]
+            if l >= 2:
+                main.wait_event(selected[l - 2])          # the score vector about to be overwritten is free
+            self.score(q_win, k, main)
+            self.accumulate(main)
+            ev = torch.cuda.Event()
+            ev.record(main)
+            scored.append(ev)
+            side_stream.wait_event(ev)
+            B.structkv_select_topk(self.indeg, self.cu, self.k_per_seq, self.keep_tail, self.idx_kv,
+                                   self.topk_workspace, side_stream)
+            ev2 = torch.cuda.Event()
+            ev2.record(side_stream)
+            selected.append(ev2)
+            self.gather(k, v, l if slots is None else slots[l], side_stream)
+        done = torch.cuda.Event()
+        done.record(side_stream)
+        main.wait_event(done)

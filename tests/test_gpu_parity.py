@@ -324,3 +324,23 @@ def test_tiny_config_full_sweep(sweep_mod, oracle):
 def test_small_sweeps(sweep_mod, oracle, name):
     wl = workloads.WORKLOADS[name]
     sweep_against_oracle(sweep_mod, oracle, wl, range(wl.n_layers), check_dormant=True)
+
+
+def test_overlapped_sweep_equals_sequential(sweep_mod):
+    # selection + gather of layer l on a side stream under the scoring of layer l+1: same bits as the plain loop
+    wl = workloads.S_BF16_RAGGED
+    L = 4
+    layers = [workloads.make_layer(wl, l % wl.n_layers, "cuda") for l in range(L)]
+    seq = make_sweep(sweep_mod, wl, n_layers_out=L)
+    for l, x in enumerate(layers):
+        seq.layer(x.q_win, x.k, x.v, slot=l)
+    torch.cuda.synchronize()
+    ovl = make_sweep(sweep_mod, wl, n_layers_out=L)
+    side = torch.cuda.Stream()
+    for _ in range(2):                                   # twice: buffers are reused across sweeps
+        ovl.reset()
+        ovl.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
+    torch.cuda.synchronize()
+    assert torch.equal(seq.centrality, ovl.centrality)
+    assert torch.equal(seq.k_cache, ovl.k_cache) and torch.equal(seq.v_cache, ovl.v_cache)
+    assert torch.equal(seq.idx_kv, ovl.idx_kv)
