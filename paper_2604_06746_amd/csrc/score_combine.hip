@@ -21,16 +21,21 @@ __device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float
   M = Mn;
 }
 
-// one workgroup per (sequence b, KV head g, block of 32 query rows); 8 threads share a row and split
-// its partial statistics, then merge in a fixed tree
-__global__ __launch_bounds__(256) void score_combine_kernel(
+// one workgroup of 1024 threads per (sequence b, KV head g, block of 32 query rows): thread = (row,
+// slot); the 32 slots of a row split its partial statistics (consecutive threads read consecutive rows,
+// the contiguous direction of the partials), then merge in a fixed order: lane pairs, then waves
+constexpr int kCombRows = 32, kCombSlots = 32;
+
+__global__ __launch_bounds__(kCombRows* kCombSlots) void score_combine_kernel(
     SeqTable seq, int G, int R, int RPC, int RC, int WK, int64_t n_chunks, int row_blocks,
     const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ row_ent) {
+  __shared__ float sM[kCombSlots / 2][kCombRows], sZ[kCombSlots / 2][kCombRows], sE[kCombSlots / 2][kCombRows];
   const int rblk = blockIdx.x % row_blocks;
   const int bg = blockIdx.x / row_blocks;
   const int b = bg / G, g = bg % G;
-  const int row = rblk * 32 + (threadIdx.x >> 3);
-  const int cl = threadIdx.x & 7;
+  const int rl = threadIdx.x & (kCombRows - 1);
+  const int slot = threadIdx.x / kCombRows;
+  const int row = rblk * kCombRows + rl;
   const int64_t c0 = seq.chunk_start[b], c1 = seq.chunk_start[b + 1];
   const int rowc = min(row, R - 1);
   const int rc = rowc / RPC, rr = rowc % RPC;
@@ -38,15 +43,30 @@ __global__ __launch_bounds__(256) void score_combine_kernel(
   float M = -1.0e30f, Z = 0.f, E = 0.f;
   const int64_t np = (c1 - c0) * WK;
   const float* base = stats + (((int64_t)grc * n_chunks + c0) * WK * 3) * RPC + rr;
-  for (int64_t p = cl; p < np; p += 8) {
+  int64_t p = slot;
+  for (; p + 3 * kCombSlots < np; p += 4 * kCombSlots) {   // four partials in flight
+    float m[4], z[4], e[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* sp = base + (p + u * kCombSlots) * 3 * RPC;
+      m[u] = sp[0]; z[u] = sp[RPC]; e[u] = sp[2 * RPC];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) merge_stats(M, Z, E, m[u], z[u], e[u]);
+  }
+  for (; p < np; p += kCombSlots) {
     const float* sp = base + p * 3 * RPC;
     merge_stats(M, Z, E, sp[0], sp[RPC], sp[2 * RPC]);
   }
-  for (int off = 1; off < 8; off <<= 1) {
-    const float M2 = __shfl_xor(M, off), Z2 = __shfl_xor(Z, off), E2 = __shfl_xor(E, off);
+  {  // the two slots of a wave
+    const float M2 = __shfl_xor(M, 32), Z2 = __shfl_xor(Z, 32), E2 = __shfl_xor(E, 32);
     merge_stats(M, Z, E, M2, Z2, E2);
   }
-  if (cl == 0 && row < R) {
+  const int wv = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) < kCombRows) { sM[wv][rl] = M; sZ[wv][rl] = Z; sE[wv][rl] = E; }
+  __syncthreads();
+  if (threadIdx.x < kCombRows && row < R) {
+    for (int k = 1; k < kCombSlots / 2; ++k) merge_stats(M, Z, E, sM[k][rl], sZ[k][rl], sE[k][rl]);
     float ent = 0.f, l2 = 0.f;
     if (c1 > c0) {
       const float lz = __log2f(Z);
@@ -59,26 +79,43 @@ __global__ __launch_bounds__(256) void score_combine_kernel(
   }
 }
 
-// grid covers the tokens in float4 units; workgroups b < B also finish Eq. 4 for sequence b
+// grid covers the tokens, V floats per thread (V = 4 for long inputs, else 1 so that enough workgroups
+// exist to use every CU); planes are added in ascending order, eight loads in flight.
+// Workgroups b < B also finish Eq. 4 for sequence b.
+template <int V>
 __global__ __launch_bounds__(256) void score_reduce_kernel(
     const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
     const float* __restrict__ row_ent, float* __restrict__ ent_head, float* __restrict__ entropy, int B,
-    int Hq, int w, int vec) {
+    int Hq, int w) {
   __shared__ float hsum[256];
-  const int64_t i4 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (vec && i4 + 3 < total) {
-    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p = 0; p < GRC; ++p) {
-      const float4 v = *reinterpret_cast<const float4*>(colsum + (int64_t)p * total + i4);
-      a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+  const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * V;
+  if (i0 < total) {   // V == 4 only when total % 4 == 0
+    float a[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) a[j] = 0.f;
+    const float* cp = colsum + i0;
+    int p = 0;
+    for (; p + 8 <= GRC; p += 8) {
+      float v[8][V];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if constexpr (V == 4) {
+          const float4 t = *reinterpret_cast<const float4*>(cp + (int64_t)(p + u) * total);
+          v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+        } else {
+          v[u][0] = cp[(int64_t)(p + u) * total];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int j = 0; j < V; ++j) a[j] += v[u][j];
     }
-    *reinterpret_cast<float4*>(indeg + i4) = a;
-  } else {
-    for (int64_t i = i4; i < min(i4 + 4, total); ++i) {
-      float a = 0.f;
-      for (int p = 0; p < GRC; ++p) a += colsum[(int64_t)p * total + i];
-      indeg[i] = a;
-    }
+    for (; p < GRC; ++p)
+#pragma unroll
+      for (int j = 0; j < V; ++j) a[j] += cp[(int64_t)p * total + j];
+    if constexpr (V == 4) *reinterpret_cast<float4*>(indeg + i0) = make_float4(a[0], a[1], a[2], a[3]);
+    else indeg[i0] = a[0];
   }
   for (int b = blockIdx.x; b < B; b += gridDim.x) {   // uniform per workgroup
     // eight lanes share a head: each sums every eighth window row, then a fixed shuffle tree
@@ -135,10 +172,10 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, 
 
 hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                                 const float* stats, float* lse2, float* row_ent, hipStream_t st) {
-  const int row_blocks = (int)ceil_div(p.R, 32);
+  const int row_blocks = (int)ceil_div(p.R, kCombRows);
   const int64_t blocks = (int64_t)seq.batch * s.n_kv_heads * row_blocks;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, st, seq, s.n_kv_heads, p.R,
+  hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)blocks), dim3(kCombRows * kCombSlots), 0, st, seq, s.n_kv_heads, p.R,
                      p.RPC, p.RC, p.WK, p.n_chunks, row_blocks, stats, lse2, row_ent);
   return hipGetLastError();
 }
@@ -146,18 +183,25 @@ hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, con
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                                const float* colsum, int64_t total, float* indeg, const float* row_ent,
                                float* ent_head, float* entropy, hipStream_t st) {
-  int64_t blocks = ceil_div(ceil_div(total, 4), 256);
+  const bool vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum) & 15) == 0 &&
+                   total >= (int64_t)4 * 256 * 1024;
+  int64_t blocks = ceil_div(ceil_div(total, vec ? 4 : 1), 256);
   if (blocks == 0) blocks = 1;
-  const int vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum) & 15) == 0;
-  hipLaunchKernelGGL(score_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                     s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
-                     s.window, vec);
+  if (vec)
+    hipLaunchKernelGGL(score_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
+                       s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
+                       s.window);
+  else
+    hipLaunchKernelGGL(score_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
+                       s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
+                       s.window);
   return hipGetLastError();
 }
 
 hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  const int vec = (((uintptr_t)c | (uintptr_t)d) & 15) == 0;
+  // four floats per thread only when that still leaves enough workgroups to use every CU
+  const int vec = (((uintptr_t)c | (uintptr_t)d) & 15) == 0 && n >= (int64_t)4 * 256 * 1024;
   const int64_t work = vec ? ceil_div(n, 4) : n;
   hipLaunchKernelGGL(accumulate_kernel, dim3((unsigned)ceil_div(work, 256)), dim3(256), 0, st, c, d, n,
                      lambda, inv_w, vec);
