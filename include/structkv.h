@@ -97,6 +97,21 @@ structkv_status structkv_accumulate_centrality(float* centrality, const float* i
                                                void* stream);
 
 /*
+ * structkv_score_layer followed by structkv_accumulate_centrality in one call (paper Eq. 1-4 and the
+ * recurrence of Alg. 1 line 6): the kernel that forms indeg_out also updates
+ *   centrality[t] = lambda*centrality[t] + inv_w*indeg_out[t]
+ * with the same arithmetic, so every output is bit-identical to the two separate calls; it saves one
+ * launch and one read of indeg per layer.  Arguments as for those two entry points; centrality
+ * [total] fp32 in/out, non-NULL whenever batch > 0, must not alias indeg_out.
+ */
+structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, const void* q_win, const void* k,
+                                                int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                                const int64_t* cu_seqlens, float* indeg_out, float* centrality,
+                                                float lambda, float inv_w, float* entropy_out,
+                                                float* entropy_per_head_out, void* workspace,
+                                                size_t workspace_bytes, void* stream);
+
+/*
  * Token selection (paper Eq. 10 on the centrality, Eq. 13 on a layer's scores): per sequence b the
  * k_b largest of scores[cu[b] .. cu[b+1]-keep_tail) -- ties go to the lower index -- united with the
  * last keep_tail positions (the observation window I_win).  Written in ascending order as

@@ -25,7 +25,8 @@ STRUCTKV_MAX_BATCH = 64
 
 EXPORTS = (
     "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
-    "structkv_accumulate_centrality", "structkv_select_topk", "structkv_gather_kv",
+    "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_select_topk",
+    "structkv_gather_kv",
     "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
 )
 
@@ -60,6 +61,9 @@ _lib.structkv_debug_score_steps.restype = _i32
 _lib.structkv_debug_score_steps.argtypes = _lib.structkv_score_layer.argtypes + [_i32]
 _lib.structkv_accumulate_centrality.restype = _i32
 _lib.structkv_accumulate_centrality.argtypes = [_vp, _vp, _i64, _f32, _f32, _vp]
+_lib.structkv_score_layer_accumulate.restype = _i32
+_lib.structkv_score_layer_accumulate.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _f32, _f32, _vp,
+                                                 _vp, _vp, _sz, _vp]
 _lib.structkv_select_topk.restype = _i32
 _lib.structkv_select_topk.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.structkv_gather_kv.restype = _i32
@@ -142,6 +146,21 @@ def structkv_accumulate_centrality(centrality: torch.Tensor, indeg: torch.Tensor
     assert centrality.numel() == indeg.numel()
     _check(_lib.structkv_accumulate_centrality(_ptr(centrality), _ptr(indeg), centrality.numel(), lam, inv_w,
                                                _stream(stream)))
+
+
+def structkv_score_layer_accumulate(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
+                                    cu_seqlens: Sequence[int], indeg_out: torch.Tensor, centrality: torch.Tensor,
+                                    lam: float, inv_w: float, entropy_out: torch.Tensor,
+                                    entropy_per_head_out: Optional[torch.Tensor], workspace: torch.Tensor,
+                                    stream=None) -> None:
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous()
+    assert centrality.numel() == indeg_out.numel()
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_score_layer_accumulate(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                                len(cu_seqlens) - 1, cu, _ptr(indeg_out), _ptr(centrality), lam,
+                                                inv_w, _ptr(entropy_out), _ptr(entropy_per_head_out),
+                                                _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                _stream(stream)))
 
 
 def structkv_select_topk(scores: torch.Tensor, cu_seqlens: Sequence[int], k_per_seq: Sequence[int],

@@ -117,7 +117,8 @@ bool mfma_eligible(const structkv_shape& s, const void* q, const void* k, int64_
 structkv_status run_score(const structkv_shape* shape, const void* q_win, const void* k, int64_t ksh,
                           int64_t kst, const SeqTable& seq_in, float* indeg, float* entropy,
                           float* ent_head_out, float* probs, void* ws, size_t ws_bytes, hipStream_t st,
-                          int step_mask = 15) {
+                          int step_mask = 15, float* centrality = nullptr, float lambda = 0.f,
+                          float inv_w = 0.f) {
   const structkv_shape& s = *shape;
   SeqTable seq = seq_in;
   const int B = seq.batch;
@@ -149,7 +150,8 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   if (step_mask & 4)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, probs, 2, st));
   if (step_mask & 8)
-    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, st));
+    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, centrality,
+                                      lambda, inv_w, st));
   return STRUCTKV_OK;
 }
 
@@ -184,7 +186,8 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
                                         int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
                                         const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                         float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
-                                        void* stream, int step_mask) {
+                                        void* stream, int step_mask, float* centrality = nullptr,
+                                        float lambda = 0.f, float inv_w = 0.f) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -207,7 +210,8 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
   if (!workspace || ((uintptr_t)workspace & 255))
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg_out, entropy_out,
-                   entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask);
+                   entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask,
+                   centrality, lambda, inv_w);
 }
 
 structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
@@ -217,6 +221,24 @@ structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_
                                      void* stream) {
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
                           entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15);
+}
+
+structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, const void* q_win, const void* k,
+                                                int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                                const int64_t* cu_seqlens, float* indeg_out, float* centrality,
+                                                float lambda, float inv_w, float* entropy_out,
+                                                float* entropy_per_head_out, void* workspace,
+                                                size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (!(lambda > 0.f && lambda <= 1.f)) return fail(STRUCTKV_ERR_INVALID_ARG, "lambda must be in (0,1]");
+  if (!(inv_w > 0.f) || !std::isfinite(inv_w)) return fail(STRUCTKV_ERR_INVALID_ARG, "inv_w must be > 0");
+  if (batch != 0 && (!centrality || ((uintptr_t)centrality & 3)))
+    return fail(STRUCTKV_ERR_INVALID_ARG, "centrality is NULL or not 4-byte aligned");
+  if (centrality && centrality == indeg_out)
+    return fail(STRUCTKV_ERR_INVALID_ARG, "centrality must not alias indeg_out");
+  return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15, centrality,
+                          lambda, inv_w);
 }
 
 structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,

@@ -2,7 +2,8 @@
 //   combine : merge the per-key-chunk softmax statistics of every query row into
 //             lse2 = M + log2 Z (what pass 2 normalises with) and the row entropies of Eq. 4.
 //   reduce  : D_j = sum over KV heads / row-chunks of the pass-2 column sums (Eq. 2 without 1/w),
-//             plus the means over window rows and heads that finish Eq. 4.
+//             plus the means over window rows and heads that finish Eq. 4; optionally also the
+//             centrality update below on the value it has just formed.
 //   accumulate : C <- lambda C + inv_w D   (Alg. 1 line 6 / Eq. 3).
 #include "common.h"
 
@@ -81,18 +82,27 @@ __global__ __launch_bounds__(kCombRows* kCombSlots) void score_combine_kernel(
 
 // grid covers the tokens, V floats per thread (V = 4 for long inputs, else 1 so that enough workgroups
 // exist to use every CU); planes are added in ascending order, eight loads in flight.
-// Workgroups b < B also finish Eq. 4 for sequence b.
+// Workgroups b < B also finish Eq. 4 for sequence b.  With `cen` != NULL the kernel also applies
+// C <- lambda C + inv_w D with the arithmetic of accumulate_kernel (one fma on the rounded product).
 template <int V>
 __global__ __launch_bounds__(256) void score_reduce_kernel(
     const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
     const float* __restrict__ row_ent, float* __restrict__ ent_head, float* __restrict__ entropy, int B,
-    int Hq, int w) {
+    int Hq, int w, float* __restrict__ cen, float lambda, float inv_w) {
   __shared__ float hsum[256];
   const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * V;
   if (i0 < total) {   // V == 4 only when total % 4 == 0
-    float a[V];
+    float a[V], c[V];
 #pragma unroll
     for (int j = 0; j < V; ++j) a[j] = 0.f;
+    if (cen) {
+      if constexpr (V == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(cen + i0);
+        c[0] = t.x; c[1] = t.y; c[2] = t.z; c[3] = t.w;
+      } else {
+        c[0] = cen[i0];
+      }
+    }
     const float* cp = colsum + i0;
     int p = 0;
     for (; p + 8 <= GRC; p += 8) {
@@ -116,6 +126,12 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
       for (int j = 0; j < V; ++j) a[j] += cp[(int64_t)p * total + j];
     if constexpr (V == 4) *reinterpret_cast<float4*>(indeg + i0) = make_float4(a[0], a[1], a[2], a[3]);
     else indeg[i0] = a[0];
+    if (cen) {
+#pragma unroll
+      for (int j = 0; j < V; ++j) c[j] = fmaf(lambda, c[j], inv_w * a[j]);
+      if constexpr (V == 4) *reinterpret_cast<float4*>(cen + i0) = make_float4(c[0], c[1], c[2], c[3]);
+      else cen[i0] = c[0];
+    }
   }
   for (int b = blockIdx.x; b < B; b += gridDim.x) {   // uniform per workgroup
     // eight lanes share a head: each sums every eighth window row, then a fixed shuffle tree
@@ -182,19 +198,20 @@ hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, con
 
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                                const float* colsum, int64_t total, float* indeg, const float* row_ent,
-                               float* ent_head, float* entropy, hipStream_t st) {
-  const bool vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum) & 15) == 0 &&
+                               float* ent_head, float* entropy, float* centrality, float lambda, float inv_w,
+                               hipStream_t st) {
+  const bool vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum | (uintptr_t)centrality) & 15) == 0 &&
                    total >= (int64_t)4 * 256 * 1024;
   int64_t blocks = ceil_div(ceil_div(total, vec ? 4 : 1), 256);
   if (blocks == 0) blocks = 1;
   if (vec)
     hipLaunchKernelGGL(score_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
                        s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
-                       s.window);
+                       s.window, centrality, lambda, inv_w);
   else
     hipLaunchKernelGGL(score_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
                        s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
-                       s.window);
+                       s.window, centrality, lambda, inv_w);
   return hipGetLastError();
 }
 

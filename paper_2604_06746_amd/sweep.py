@@ -56,6 +56,11 @@ class LayerSweep:
     def accumulate(self, stream=None) -> None:
         B.structkv_accumulate_centrality(self.centrality, self.indeg, self.lam, 1.0 / self.w, stream)
 
+    def score_accumulate(self, q_win: torch.Tensor, k: torch.Tensor, stream=None) -> None:
+        """score() then accumulate() as one call of the library (same results, one launch fewer)."""
+        B.structkv_score_layer_accumulate(self.shape, q_win, k, self.cu, self.indeg, self.centrality, self.lam,
+                                          1.0 / self.w, self.entropy, self.entropy_per_head, self.workspace, stream)
+
     def select_kv(self, stream=None) -> None:
         """Eq. 13: per-layer storage indices from this layer's scores."""
         B.structkv_select_topk(self.indeg, self.cu, self.k_per_seq, self.keep_tail, self.idx_kv,
@@ -72,8 +77,7 @@ class LayerSweep:
 
     def layer(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, slot: int = 0, stream=None) -> None:
         """One pass of the hot path over one layer: score -> accumulate -> select -> gather."""
-        self.score(q_win, k, stream)
-        self.accumulate(stream)
+        self.score_accumulate(q_win, k, stream)
         self.select_kv(stream)
         self.gather(k, v, slot, stream)
 
@@ -90,8 +94,7 @@ class LayerSweep:
             self.indeg = self._indeg2[l & 1]
             if l >= 2:
                 main.wait_event(selected[l - 2])          # the score vector about to be overwritten is free
-            self.score(q_win, k, main)
-            self.accumulate(main)
+            self.score_accumulate(q_win, k, main)
             ev = torch.cuda.Event()
             ev.record(main)
             scored.append(ev)

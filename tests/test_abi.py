@@ -91,6 +91,17 @@ def test_invalid_arguments_are_rejected_on_the_host(B):
     assert acc(fake, fake, -1, 0.9, 0.1, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert acc(None, None, 0, 0.9, 0.1, None) == B.STRUCTKV_OK
 
+    def fused(cen=fake, indeg=ctypes.c_void_p(8192), lam=0.9, inv_w=0.1, batch=1):
+        return lib.structkv_score_layer_accumulate(ctypes.byref(ok_shape), fake, fake, 100 * 128, 128, batch, cu,
+                                                   indeg, cen, lam, inv_w, fake, None, None, ws_bytes, None)
+    assert fused(lam=0.0) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(inv_w=-1.0) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(cen=None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(cen=ctypes.c_void_p(4098)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(cen=fake, indeg=fake) == B.STRUCTKV_ERR_INVALID_ARG and "alias" in B.structkv_last_error()
+    assert fused() == B.STRUCTKV_ERR_WORKSPACE            # everything else valid: stops at the NULL workspace
+    assert fused(cen=None, batch=0) == B.STRUCTKV_OK
+
     topk = lib.structkv_select_topk
     assert topk(fake, 1, cu, (i64 * 1)(101), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert topk(fake, 1, cu, (i64 * 1)(90), 32, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG

@@ -326,6 +326,21 @@ def test_small_sweeps(sweep_mod, oracle, name):
     sweep_against_oracle(sweep_mod, oracle, wl, range(wl.n_layers), check_dormant=True)
 
 
+@pytest.mark.parametrize("name", ["s_bf16_ragged", "s_f32_ragged", "s_bf16_gqa4"])
+def test_fused_score_accumulate_equals_two_calls(sweep_mod, name):
+    # the one-call form must give the bits of score_layer followed by accumulate_centrality
+    wl = workloads.WORKLOADS[name]
+    two, one = make_sweep(sweep_mod, wl), make_sweep(sweep_mod, wl)
+    for l in range(3):
+        x = workloads.make_layer(wl, l % wl.n_layers, "cuda")
+        two.score(x.q_win, x.k)
+        two.accumulate()
+        one.score_accumulate(x.q_win, x.k)
+        torch.cuda.synchronize()
+        assert torch.equal(two.indeg, one.indeg) and torch.equal(two.centrality, one.centrality)
+        assert torch.equal(two.entropy, one.entropy) and torch.equal(two.entropy_per_head, one.entropy_per_head)
+
+
 def test_overlapped_sweep_equals_sequential(sweep_mod):
     # selection + gather of layer l on a side stream under the scoring of layer l+1: same bits as the plain loop
     wl = workloads.S_BF16_RAGGED
