@@ -1,32 +1,35 @@
 // Exact, deterministic top-k selection (paper Eq. 10 / Eq. 13): radix select on order-preserving
 // 32-bit keys (three digit passes, 11/11/10 bits from the top), then an index-ordered compaction.
 //
-// Two launches per call.  `topk_init_kernel` zeroes the histograms and barrier words and writes the
-// kept window.  `topk_select_kernel` is one resident grid (at most 1024 workgroups in all, so every
-// workgroup is on the chip at once) in which the workgroups of a sequence move through five phases
-// separated by a counter barrier in global memory:
-//   digit histogram (LDS, merged with integer atomics)  x3, each followed by every workgroup scanning the
-//   2048 bins from the top to narrow the search;  per-workgroup counts of keys above / equal to the
-//   threshold key;  ordered write (each workgroup adds the counts of the workgroups before it).
-// Ties at the threshold go to the lowest indices; output is ascending; no floating-point atomics.
-// The barrier wait is bounded: a workgroup that waits too long gives up, raises an error word in the
-// workspace and still runs to the end, so the kernel always terminates.
+// Five short launches per call; the stream order between them is the only synchronisation (no
+// workgroup ever waits for another one, so there is no residency requirement and nothing can hang):
+//   init   : zero the three digit histograms, write the kept window
+//   hist0  : histogram of the top 11 key bits (LDS, merged into global memory with integer atomics)
+//   hist1  : every workgroup scans histogram 0 from the top to find the digit of the k-th key, then
+//            histograms the next 11 bits of the keys that carry that digit
+//   hist2  : same for digit 1; then one sweep that counts the keys above the 22-bit prefix and
+//            histograms the last 10 bits of the keys equal to it.  Each workgroup also publishes the
+//            suffix sums of its own last-digit histogram, so that once the last digit T is known
+//            anyone can read "keys of workgroup w above T" and "equal to T" with two loads
+//   write  : find the last digit, add up the counts of the workgroups before this one, and write the
+//            selected indices in ascending order.
+// Ties at the threshold go to the lowest indices; no floating-point atomics anywhere.
 #include "common.h"
 
 namespace skv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kBins = 2048;
-constexpr int kMaxBlocksPerSeq = 128;
-constexpr int kMaxBlocksTotal = 1024;
-constexpr int kTargetPerBlock = 2048;        // scores per workgroup when the sequence is short enough
-constexpr uint32_t kSpinLimit = 1u << 22;    // barrier polls (about a microsecond each) before a workgroup gives up
+constexpr int kBins = 2048;               // digits 0 and 1: 11 bits
+constexpr int kLowBins = 1024;            // digit 2: 10 bits
+constexpr int kTargetPerBlock = 2048;     // scores per workgroup while the sequence is short enough
+constexpr int kMaxBlocksPerSeq = 1024;    // beyond that a workgroup's share grows instead
 
 struct TopkWs {
-  uint32_t* hist;     // [B][3][kBins]
-  uint32_t* bar;      // [B][4]: arrivals, error flag, unused, unused
-  uint32_t* blkcnt;   // [total_blocks][2] (above, equal)
+  uint32_t* hist;    // [B][3][kBins]
+  uint32_t* state;   // [B][4]: digit 0, k left after it, 22-bit prefix, k left after it
+  uint32_t* suf;     // [blocks][kLowBins]: suffix sums of the workgroup's last-digit histogram
+  uint32_t* meta;    // [blocks][2]: keys above the 22-bit prefix, keys equal to it
 };
 
 __device__ inline uint32_t score_key(float f) {
@@ -35,8 +38,28 @@ __device__ inline uint32_t score_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);    // larger float <=> larger key
 }
 
-__device__ inline uint32_t ld_agent(const uint32_t* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// the calling workgroup's sequence and its contiguous share [lo, hi) of the prefix that is searched
+struct Share {
+  int b;
+  uint32_t nblk, blk, first;   // workgroups of the sequence, rank of this one, global id of rank 0
+  int64_t lo, hi;
+  const float* sc;
+};
+
+__device__ inline Share my_share(const float* scores, const SeqTable& seq, int keep_tail) {
+  Share s;
+  int b = 0;
+  while (b + 1 < seq.batch && (int)blockIdx.x >= seq.chunk_start[b + 1]) ++b;
+  s.b = b;
+  s.first = (uint32_t)seq.chunk_start[b];
+  s.nblk = (uint32_t)(seq.chunk_start[b + 1] - seq.chunk_start[b]);
+  s.blk = blockIdx.x - s.first;
+  const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
+  const int64_t per = (m + s.nblk - 1) / s.nblk;
+  s.lo = min(m, (int64_t)s.blk * per);
+  s.hi = min(m, s.lo + per);
+  s.sc = scores + seq.cu[b];
+  return s;
 }
 
 __global__ __launch_bounds__(kThreads) void topk_init_kernel(SeqTable seq, int keep_tail, TopkWs ws,
@@ -45,7 +68,6 @@ __global__ __launch_bounds__(kThreads) void topk_init_kernel(SeqTable seq, int k
   const int tid = blockIdx.x * kThreads + threadIdx.x;
   const int stride = gridDim.x * kThreads;
   for (int i = tid; i < 3 * kBins; i += stride) ws.hist[(size_t)b * 3 * kBins + i] = 0u;
-  if (tid < 4) ws.bar[b * 4 + tid] = 0u;
   const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
   for (int i = tid; i < keep_tail; i += stride)
     idx_out[seq.out_off[b] + seq.k[b] + i] = (int32_t)(m + i);
@@ -70,36 +92,20 @@ __device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t* sh /*[>=4]*/, u
   return w0 + w1 + w2 + w3;
 }
 
-// All workgroups of a sequence meet here; `phase` counts from 1.  Arrivals only ever grow during a call,
-// so phase p is complete when the counter reaches p * nblk.
-__device__ inline void seq_barrier(uint32_t* bar, uint32_t nblk, uint32_t phase) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    __threadfence();
-    atomicAdd(&bar[0], 1u);
-    const uint32_t target = phase * nblk;
-    uint32_t spins = 0;
-    while (ld_agent(&bar[0]) < target) {
-      if (++spins > kSpinLimit) { atomicExch(&bar[1], 1u); break; }   // give up rather than hang
-    }
-    __threadfence();
-  }
-  __syncthreads();
-}
-
-// Scan `nb` bins of a merged histogram from the top until `krem` candidates are covered.
-// Returns the bin (all threads), and how many candidates lie above it.
-__device__ inline void select_bin(const uint32_t* gh, int nb, uint32_t krem, uint32_t* scan, uint32_t* res,
-                                  uint32_t* bin_out, uint32_t* above_out) {
+// Scan `nb` bins of a merged histogram from the top until `krem` keys are covered.
+// Returns the bin (all threads), and how many keys lie above it.
+__device__ inline void select_bin(const uint32_t* __restrict__ gh, int nb, uint32_t krem, uint32_t* scan,
+                                  uint32_t* res, uint32_t* bin_out, uint32_t* above_out) {
   const int t = threadIdx.x;
   const int per = nb / kThreads;   // 8 or 4
   uint32_t mine[8];
   uint32_t sum = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    mine[i] = i < per ? ld_agent(&gh[nb - 1 - (t * per + i)]) : 0u;
+    mine[i] = i < per ? gh[nb - 1 - (t * per + i)] : 0u;
     sum += mine[i];
   }
+  if (t == 0) { res[0] = 0u; res[1] = 0u; }
   uint32_t excl;
   block_excl_scan(sum, scan, &excl);
   if (excl < krem && excl + sum >= krem) {
@@ -119,82 +125,189 @@ __device__ inline void select_bin(const uint32_t* gh, int nb, uint32_t krem, uin
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kThreads) void topk_select_kernel(const float* __restrict__ scores, SeqTable seq,
-                                                               int keep_tail, TopkWs ws,
-                                                               int32_t* __restrict__ idx_out) {
+// add a workgroup's LDS histogram into the merged one
+__device__ inline void merge_hist(const uint32_t* h, int nb, uint32_t* __restrict__ gh) {
+  for (int i = threadIdx.x; i < nb; i += kThreads)
+    if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
+// A workgroup's share normally fits eight scores per thread; those are loaded into registers before the
+// histogram scan so that the two latencies overlap.  Longer shares (capped workgroup count) loop instead.
+constexpr int kPerThread = kTargetPerBlock / kThreads;
+
+// thread t takes scores lo + t, lo + t + 256, ...
+__device__ inline bool preload_strided(const Share& s, float (&v)[kPerThread]) {
+  const bool fast = s.hi - s.lo <= kTargetPerBlock;
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int64_t j = s.lo + threadIdx.x + i * kThreads;
+      v[i] = j < s.hi ? s.sc[j] : 0.f;
+    }
+  }
+  return fast;
+}
+
+template <class F>
+__device__ inline void for_each_strided(const Share& s, const float (&v)[kPerThread], bool fast, F f) {
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+      if (s.lo + threadIdx.x + i * kThreads < s.hi) f(score_key(v[i]));
+  } else {
+    for (int64_t j = s.lo + threadIdx.x; j < s.hi; j += kThreads) f(score_key(s.sc[j]));
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void topk_hist0_kernel(const float* __restrict__ scores, SeqTable seq,
+                                                              int keep_tail, TopkWs ws) {
   __shared__ uint32_t h[kBins];
-  __shared__ uint32_t scan[kThreads];
+  const Share s = my_share(scores, seq, keep_tail);
+  const int t = threadIdx.x;
+  float v[kPerThread];
+  const bool fast = preload_strided(s, v);
+  for (int i = t; i < kBins; i += kThreads) h[i] = 0u;
+  __syncthreads();
+  for_each_strided(s, v, fast, [&](uint32_t key) { atomicAdd(&h[key >> 21], 1u); });
+  __syncthreads();
+  merge_hist(h, kBins, ws.hist + (size_t)s.b * 3 * kBins);
+}
+
+__global__ __launch_bounds__(kThreads) void topk_hist1_kernel(const float* __restrict__ scores, SeqTable seq,
+                                                              int keep_tail, TopkWs ws) {
+  __shared__ uint32_t h[kBins];
+  __shared__ uint32_t scan[4];
+  __shared__ uint32_t res[2];
+  const Share s = my_share(scores, seq, keep_tail);
+  const int t = threadIdx.x;
+  uint32_t* gh = ws.hist + (size_t)s.b * 3 * kBins;
+  float v[kPerThread];
+  const bool fast = preload_strided(s, v);
+  for (int i = t; i < kBins; i += kThreads) h[i] = 0u;
+  uint32_t bin0, above0;
+  select_bin(gh, kBins, (uint32_t)seq.k[s.b], scan, res, &bin0, &above0);   // its barriers cover h[] = 0
+  if (s.blk == 0 && t == 0) {
+    ws.state[s.b * 4 + 0] = bin0;
+    ws.state[s.b * 4 + 1] = (uint32_t)seq.k[s.b] - above0;
+  }
+  for_each_strided(s, v, fast, [&](uint32_t key) {
+    if ((key >> 21) == bin0) atomicAdd(&h[(key >> 10) & (kBins - 1)], 1u);
+  });
+  __syncthreads();
+  merge_hist(h, kBins, gh + kBins);
+}
+
+__global__ __launch_bounds__(kThreads) void topk_hist2_kernel(const float* __restrict__ scores, SeqTable seq,
+                                                              int keep_tail, TopkWs ws) {
+  __shared__ uint32_t h[kLowBins];
+  __shared__ uint32_t scan[4];
+  __shared__ uint32_t res[2];
+  __shared__ uint32_t above_cnt;
+  const Share s = my_share(scores, seq, keep_tail);
+  const int t = threadIdx.x;
+  uint32_t* gh = ws.hist + (size_t)s.b * 3 * kBins;
+  float v[kPerThread];
+  const bool fast = preload_strided(s, v);
+  for (int i = t; i < kLowBins; i += kThreads) h[i] = 0u;
+  if (t == 0) above_cnt = 0u;
+  const uint32_t bin0 = ws.state[s.b * 4 + 0], krem0 = ws.state[s.b * 4 + 1];
+  uint32_t bin1, above1;
+  select_bin(gh + kBins, kBins, krem0, scan, res, &bin1, &above1);   // its barriers cover h[], above_cnt = 0
+  const uint32_t prefix = (bin0 << 11) | bin1;     // the top 22 bits of the k-th largest key
+  if (s.blk == 0 && t == 0) {
+    ws.state[s.b * 4 + 2] = prefix;
+    ws.state[s.b * 4 + 3] = krem0 - above1;
+  }
+  uint32_t above = 0;
+  for_each_strided(s, v, fast, [&](uint32_t key) {
+    const uint32_t hi = key >> 10;
+    above += hi > prefix;
+    if (hi == prefix) atomicAdd(&h[key & (kLowBins - 1)], 1u);
+  });
+  if (above) atomicAdd(&above_cnt, above);
+  __syncthreads();
+  merge_hist(h, kLowBins, gh + 2 * kBins);
+  // suffix sums of h: thread t owns the four bins 1023-4t .. 1020-4t (descending), scanned from the top
+  uint32_t own[4];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { own[i] = h[kLowBins - 1 - (4 * t + i)]; sum += own[i]; }
+  uint32_t run;
+  const uint32_t ncand = block_excl_scan(sum, scan, &run);
+  if (ncand) {
+    uint32_t* suf = ws.suf + (size_t)blockIdx.x * kLowBins;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { run += own[i]; suf[kLowBins - 1 - (4 * t + i)] = run; }
+  }
+  if (t == 0) {
+    ws.meta[2 * (size_t)blockIdx.x] = above_cnt;
+    ws.meta[2 * (size_t)blockIdx.x + 1] = ncand;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __restrict__ scores, SeqTable seq,
+                                                              int keep_tail, TopkWs ws,
+                                                              int32_t* __restrict__ idx_out) {
+  __shared__ uint32_t scan[4];
   __shared__ uint32_t res[2];
   __shared__ uint32_t cnt[2];
-  int b = 0;
-  while (b + 1 < seq.batch && (int)blockIdx.x >= seq.chunk_start[b + 1]) ++b;
-  const uint32_t nblk = (uint32_t)(seq.chunk_start[b + 1] - seq.chunk_start[b]);
-  const uint32_t blk = blockIdx.x - (uint32_t)seq.chunk_start[b];
-  const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
-  const float* sc = scores + seq.cu[b];
-  uint32_t* bar = ws.bar + b * 4;
-  uint32_t* gh = ws.hist + (size_t)b * 3 * kBins;
+  const Share s = my_share(scores, seq, keep_tail);
   const int t = threadIdx.x;
-  // this workgroup's contiguous share of the sequence
-  const int64_t per = (m + nblk - 1) / nblk;
-  const int64_t lo = min(m, (int64_t)blk * per), hi = min(m, lo + per);
-
-  uint32_t prefix = 0, krem = (uint32_t)seq.k[b];
-  // ---- three digit passes ----
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    const int bits = pass == 2 ? 10 : 11;
-    const int nb = 1 << bits;
-    for (int i = t; i < nb; i += kThreads) h[i] = 0u;
-    __syncthreads();
-    for (int64_t j = lo + t; j < hi; j += kThreads) {
-      const uint32_t key = score_key(sc[j]);
-      const bool match = pass == 0 ? true : ((key >> (shift + bits)) == prefix);
-      if (match) atomicAdd(&h[(key >> shift) & (nb - 1)], 1u);
-    }
-    __syncthreads();
-    for (int i = t; i < nb; i += kThreads)
-      if (h[i]) atomicAdd(&gh[pass * kBins + i], h[i]);
-    seq_barrier(bar, nblk, (uint32_t)pass + 1);
-    uint32_t bin, above;
-    select_bin(gh + pass * kBins, nb, krem, scan, res, &bin, &above);
-    prefix = (prefix << bits) | bin;
-    krem -= above;
+  const uint32_t* gh = ws.hist + (size_t)s.b * 3 * kBins;
+  if (t == 0) { cnt[0] = 0u; cnt[1] = 0u; }
+  // this workgroup's share; thread t owns a contiguous slice of it (loaded before the histogram scan)
+  const int64_t sub = (s.hi - s.lo + kThreads - 1) / kThreads;
+  const int64_t tlo = min(s.hi, s.lo + t * sub), thi = min(s.hi, tlo + sub);
+  const bool fast = sub <= kPerThread;
+  float v[kPerThread];
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) v[i] = tlo + i < thi ? s.sc[tlo + i] : 0.f;
   }
-  const uint32_t T = prefix;      // the k-th largest key
-  const uint32_t need = krem;     // how many keys equal to T are taken (lowest indices first)
+  const uint32_t prefix = ws.state[s.b * 4 + 2], krem1 = ws.state[s.b * 4 + 3];
+  uint32_t t10, above2;
+  select_bin(gh + 2 * kBins, kLowBins, krem1, scan, res, &t10, &above2);   // its barriers cover cnt[] = 0
+  const uint32_t T = (prefix << 10) | t10;   // the k-th largest key
+  const uint32_t need = krem1 - above2;      // how many keys equal to T are taken (lowest indices first)
 
-  // ---- counts of this workgroup's share; thread t owns a contiguous slice of it ----
-  const int64_t sub = (hi - lo + kThreads - 1) / kThreads;
-  const int64_t tlo = min(hi, lo + t * sub), thi = min(hi, tlo + sub);
-  uint32_t gt = 0, eq = 0;
-  for (int64_t j = tlo; j < thi; ++j) {
-    const uint32_t key = score_key(sc[j]);
-    gt += key > T;
-    eq += key == T;
-  }
-  uint32_t gt_before, eq_before;
-  const uint32_t gt_blk = block_excl_scan(gt, scan, &gt_before);
-  const uint32_t eq_blk = block_excl_scan(eq, scan, &eq_before);
-  uint32_t* bc = ws.blkcnt + (size_t)seq.chunk_start[b] * 2;
-  if (t == 0) {
-    __hip_atomic_store(&bc[2 * blk], gt_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&bc[2 * blk + 1], eq_blk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    cnt[0] = 0u; cnt[1] = 0u;
-  }
-  seq_barrier(bar, nblk, 4u);
-
-  // ---- ordered write: counts of the workgroups before this one, then of the threads before this one ----
+  // selected keys in the workgroups before this one
   uint32_t g0 = 0, e0 = 0;
-  for (uint32_t i = t; i < blk; i += kThreads) { g0 += ld_agent(&bc[2 * i]); e0 += ld_agent(&bc[2 * i + 1]); }
+  for (uint32_t i = t; i < s.blk; i += kThreads) {
+    const size_t w = (size_t)s.first + i;
+    g0 += ws.meta[2 * w];
+    if (ws.meta[2 * w + 1]) {
+      const uint32_t* suf = ws.suf + w * kLowBins;
+      const uint32_t ge = suf[t10];
+      const uint32_t gt = t10 + 1 < (uint32_t)kLowBins ? suf[t10 + 1] : 0u;
+      g0 += gt;
+      e0 += ge - gt;
+    }
+  }
   if (g0) atomicAdd(&cnt[0], g0);
   if (e0) atomicAdd(&cnt[1], e0);
-  __syncthreads();
+
+  uint32_t gt = 0, eq = 0;
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const uint32_t key = score_key(v[i]);
+      gt += tlo + i < thi && key > T;
+      eq += tlo + i < thi && key == T;
+    }
+  } else {
+    for (int64_t j = tlo; j < thi; ++j) {
+      const uint32_t key = score_key(s.sc[j]);
+      gt += key > T;
+      eq += key == T;
+    }
+  }
+  uint32_t gt_before, eq_before;
+  block_excl_scan(gt, scan, &gt_before);
+  block_excl_scan(eq, scan, &eq_before);   // the barriers inside also order the cnt[] atomics above
   gt_before += cnt[0];
   eq_before += cnt[1];
-  int32_t* out = idx_out + seq.out_off[b];
-  for (int64_t j = tlo; j < thi; ++j) {
-    const uint32_t key = score_key(sc[j]);
+  int32_t* out = idx_out + seq.out_off[s.b];
+  auto place = [&](uint32_t key, int64_t j) {
     if (key > T) {
       out[gt_before + min(eq_before, need)] = (int32_t)j;
       ++gt_before;
@@ -202,25 +315,31 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(const float* __re
       if (eq_before < need) out[gt_before + eq_before] = (int32_t)j;
       ++eq_before;
     }
+  };
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+      if (tlo + i < thi) place(score_key(v[i]), tlo + i);
+  } else {
+    for (int64_t j = tlo; j < thi; ++j) place(score_key(s.sc[j]), j);
   }
 }
 
-TopkWs carve(void* ws, int B) {
-  TopkWs w;
-  uint8_t* p = (uint8_t*)ws;
-  w.hist = (uint32_t*)p;   p += align_up(sizeof(uint32_t) * 3 * (size_t)B * kBins, 256);
-  w.bar = (uint32_t*)p;    p += align_up(sizeof(uint32_t) * 4 * (size_t)B, 256);
-  w.blkcnt = (uint32_t*)p;
-  return w;
+// upper bound of the workgroups one call launches
+size_t max_blocks(int batch, int64_t total_tokens) {
+  const size_t B = (size_t)(batch > 0 ? batch : 1);
+  size_t nb = (size_t)(total_tokens / kTargetPerBlock) + B;
+  if (nb > B * kMaxBlocksPerSeq) nb = B * kMaxBlocksPerSeq;
+  return nb;
 }
 
 }  // namespace
 
 size_t topk_workspace_bytes(int batch, int64_t total_tokens) {
-  (void)total_tokens;
   const size_t B = (size_t)(batch > 0 ? batch : 1);
+  const size_t nb = max_blocks(batch, total_tokens);
   return align_up(sizeof(uint32_t) * 3 * B * kBins, 256) + align_up(sizeof(uint32_t) * 4 * B, 256) +
-         align_up(sizeof(uint32_t) * 2 * (size_t)kMaxBlocksTotal, 256);
+         align_up(sizeof(uint32_t) * kLowBins * nb, 256) + align_up(sizeof(uint32_t) * 2 * nb, 256);
 }
 
 // seq.out_off must hold the output offsets, seq.k the budgets.
@@ -229,21 +348,30 @@ hipError_t launch_topk(const float* scores, const SeqTable& seq_in, int keep_tai
   SeqTable seq = seq_in;
   const int B = seq.batch;
   if (B == 0) return hipSuccess;
-  // workgroups per sequence: about kTargetPerBlock scores each, at most kMaxBlocksPerSeq, and few enough
-  // in all that the whole grid is resident at once (the phases meet at a barrier)
-  const int cap = kMaxBlocksTotal / B < kMaxBlocksPerSeq ? kMaxBlocksTotal / B : kMaxBlocksPerSeq;
+  // workgroups per sequence: about kTargetPerBlock scores each, at most kMaxBlocksPerSeq
   seq.chunk_start[0] = 0;
   for (int b = 0; b < B; ++b) {
     const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
     int64_t nblk = seq.k[b] > 0 ? ceil_div(m, kTargetPerBlock) : 0;
-    if (nblk > cap) nblk = cap;
+    if (nblk > kMaxBlocksPerSeq) nblk = kMaxBlocksPerSeq;
     seq.chunk_start[b + 1] = seq.chunk_start[b] + (int)nblk;
   }
-  TopkWs ws = carve(wsp, B);
+  const unsigned blocks = (unsigned)seq.chunk_start[B];
+  const size_t nb = max_blocks(B, seq.cu[B]);   // blocks <= nb: sum of ceil(m_b / 2048) <= total / 2048 + B
+  TopkWs ws;
+  uint8_t* p = (uint8_t*)wsp;
+  ws.hist = (uint32_t*)p;    p += align_up(sizeof(uint32_t) * 3 * (size_t)B * kBins, 256);
+  ws.state = (uint32_t*)p;   p += align_up(sizeof(uint32_t) * 4 * (size_t)B, 256);
+  ws.suf = (uint32_t*)p;     p += align_up(sizeof(uint32_t) * kLowBins * nb, 256);
+  ws.meta = (uint32_t*)p;
   hipLaunchKernelGGL(topk_init_kernel, dim3(4, B), dim3(kThreads), 0, st, seq, keep_tail, ws, idx_out);
-  if (seq.chunk_start[B] > 0)
-    hipLaunchKernelGGL(topk_select_kernel, dim3(seq.chunk_start[B]), dim3(kThreads), 0, st, scores, seq,
-                       keep_tail, ws, idx_out);
+  if (blocks > 0) {
+    hipLaunchKernelGGL(topk_hist0_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
+    hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
+    hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
+    hipLaunchKernelGGL(topk_write_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws,
+                       idx_out);
+  }
   return hipGetLastError();
 }
 

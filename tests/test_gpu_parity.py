@@ -214,7 +214,8 @@ def _topk_gpu(B, scores, lens, ks, tail):
 
 @pytest.mark.parametrize("n,k,tail", [(1000, 100, 32), (257, 1, 0), (64, 32, 32), (50, 50, 0), (10, 0, 3),
                                       (4096, 4000, 64), (4097, 17, 1), (20000, 2048, 32), (300000, 16384, 64),
-                                      (1, 1, 0), (33, 0, 33)])
+                                      (1, 1, 0), (33, 0, 33),
+                                      (2200000, 50000, 64)])      # > 1024 workgroups' worth: shares grow
 def test_topk_bit_identical_to_oracle(B, oracle, n, k, tail):
     rng = np.random.default_rng(n * 31 + k)
     for variant in ("normal", "ties", "all_equal", "tiny_range", "signed"):
