@@ -264,6 +264,9 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) v[i] = tlo + i < thi ? s.sc[tlo + i] : 0.f;
   }
+  // counts of the first workgroup this thread will add up, also requested before the scan
+  const bool has0 = (uint32_t)t < s.blk;
+  const uint2 m0 = has0 ? *reinterpret_cast<const uint2*>(ws.meta + 2 * ((size_t)s.first + t)) : make_uint2(0u, 0u);
   const uint32_t prefix = ws.state[s.b * 4 + 2], krem1 = ws.state[s.b * 4 + 3];
   uint32_t t10, above2;
   select_bin(gh + 2 * kBins, kLowBins, krem1, scan, res, &t10, &above2);   // its barriers cover cnt[] = 0
@@ -272,16 +275,20 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
 
   // selected keys in the workgroups before this one
   uint32_t g0 = 0, e0 = 0;
-  for (uint32_t i = t; i < s.blk; i += kThreads) {
-    const size_t w = (size_t)s.first + i;
-    g0 += ws.meta[2 * w];
-    if (ws.meta[2 * w + 1]) {
+  auto add_block = [&](size_t w, uint32_t above, uint32_t ncand) {
+    g0 += above;
+    if (ncand) {
       const uint32_t* suf = ws.suf + w * kLowBins;
       const uint32_t ge = suf[t10];
       const uint32_t gt = t10 + 1 < (uint32_t)kLowBins ? suf[t10 + 1] : 0u;
       g0 += gt;
       e0 += ge - gt;
     }
+  };
+  if (has0) add_block((size_t)s.first + t, m0.x, m0.y);
+  for (uint32_t i = t + kThreads; i < s.blk; i += kThreads) {
+    const size_t w = (size_t)s.first + i;
+    add_block(w, ws.meta[2 * w], ws.meta[2 * w + 1]);
   }
   if (g0) atomicAdd(&cnt[0], g0);
   if (e0) atomicAdd(&cnt[1], e0);
