@@ -142,6 +142,35 @@ structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t
                                    const int32_t* idx, void* stream);
 
 /*
+ * Structural truncation (paper Eq. 11-12): keep the hidden states and the position ids of the
+ * structural indices, in index order.
+ *   h_dst[o_b + i][:]  = h_src[cu[b] + idx[o_b + i]][:]          (hidden_dim*elem_bytes bytes, bit-exact)
+ *   pos_dst[o_b + i]   = pos_src ? pos_src[cu[b] + idx[o_b + i]] : idx[o_b + i]
+ * h_src : [total][hidden] rows, src_stride_tok elements apart; h_dst likewise with dst_stride_tok.
+ *         Both NULL skips the hidden states.
+ * pos_src : DEVICE int64 [total] position ids (for RoPE re-alignment), or NULL for the identity
+ *           0..n_b-1 of every sequence; pos_dst : DEVICE int64 [rows] or NULL to skip positions.
+ * idx, rows_per_seq, cu_seqlens, elem_bytes and the out-of-range rule: as for structkv_gather_kv.
+ */
+structkv_status structkv_truncate_hidden(const void* h_src, int64_t src_stride_tok, void* h_dst,
+                                         int64_t dst_stride_tok, int32_t hidden_dim, int32_t elem_bytes,
+                                         const int64_t* pos_src, int64_t* pos_dst, int32_t batch,
+                                         const int64_t* cu_seqlens, const int64_t* rows_per_seq,
+                                         const int32_t* idx, void* stream);
+
+/*
+ * Block-level aggregation for paged caches (paper Sec. 4.1, implementation details): the score of
+ * cache block k of sequence b is the sum of the scores (normally the centrality) of its tokens,
+ *   out[B_b + k] = sum_{t = k*block_size}^{min(n_b, (k+1)*block_size) - 1} scores[cu[b] + t],
+ *   k < ceil(n_b / block_size),  B_b = sum_{b' < b} ceil(n_b' / block_size),
+ * added left to right in fp32 (deterministic).  scores, block_scores_out : DEVICE fp32.
+ * Lowest-score blocks are then found with structkv_select_topk on block_scores_out (cu = the B_b),
+ * and kept blocks are moved with structkv_gather_kv on K/V viewed as [G][n/block_size][block_size*d].
+ */
+structkv_status structkv_block_scores(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                      int32_t block_size, float* block_scores_out, void* stream);
+
+/*
  * Test hook: the attention rows themselves (paper Eq. 1) for ONE sequence of n tokens,
  * probs_out [H_q][w][n] fp32, computed by the same kernels as structkv_score_layer.
  * H_q*w*n must not exceed 2^26.

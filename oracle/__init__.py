@@ -47,6 +47,8 @@ def _load():
         lib.skv_oracle_select_topk.argtypes = [vp, i64, i64, i64, vp]
         lib.skv_oracle_gather_rows.restype = None
         lib.skv_oracle_gather_rows.argtypes = [vp, i64, i64, vp, i64, i64, i32, i64, vp, i64, i64, i64]
+        lib.skv_oracle_block_scores.restype = None
+        lib.skv_oracle_block_scores.argtypes = [vp, i64, i64, vp]
         _lib = lib
     return _lib
 
@@ -163,3 +165,39 @@ def gather_kv(src: np.ndarray, idx_per_seq: Sequence[np.ndarray], seq_lens: Sequ
         so += int(n)
         do += len(idx)
     return dst
+
+
+def truncate_hidden(h: np.ndarray, positions: Optional[np.ndarray], idx_per_seq: Sequence[np.ndarray],
+                    seq_lens: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 11-12: keep hidden states and positions at the structural indices.
+
+    h [total, hidden] (any 2- or 4-byte dtype), positions [total] int64 or None (= 0..n_b-1 per sequence).
+    Returns (h' [rows, hidden], positions' [rows] int64), rows = sum(len(idx_b)), exact row copies.
+    """
+    h = np.ascontiguousarray(h)
+    total = h.shape[0]
+    if positions is None:
+        positions = np.concatenate([np.arange(n, dtype=np.int64) for n in seq_lens]) if len(seq_lens) else \
+            np.zeros(0, np.int64)
+    positions = np.ascontiguousarray(positions, dtype=np.int64)
+    assert positions.shape == (total,)
+    h_out = gather_kv(h[None], idx_per_seq, seq_lens)[0]
+    p_out = gather_kv(positions.view(np.int32).reshape(1, total, 2), idx_per_seq, seq_lens)[0]
+    return h_out, np.ascontiguousarray(p_out).view(np.int64).reshape(-1)
+
+
+def block_scores(scores: np.ndarray, seq_lens: Sequence[int], block: int) -> List[np.ndarray]:
+    """Sec. 4.1 (implementation details): per sequence, the sum of the scores of every cache block of
+    `block` tokens (the last block of a sequence may be shorter).  fp64."""
+    lib = _load()
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    out, off = [], 0
+    for n in seq_lens:
+        n = int(n)
+        o = np.zeros((n + block - 1) // block, dtype=np.float64)
+        if n:
+            seg = np.ascontiguousarray(scores[off:off + n])
+            lib.skv_oracle_block_scores(_ptr(seg), n, int(block), _ptr(o))
+        out.append(o)
+        off += n
+    return out

@@ -16,7 +16,10 @@
  *                                the observation window (reading: top-k over the
  *                                prefix [0, n-keep_tail), window appended, ties to the
  *                                lower index, output ascending)
- *   skv_oracle_gather_rows       Alg. 1 line 17: keep K/V rows at the selected indices
+ *   skv_oracle_gather_rows       Alg. 1 line 17: keep K/V rows at the selected indices; the same row copy
+ *                                serves Eq. 11 (hidden states and positions kept at I_struct)
+ *   skv_oracle_block_scores      Sec. 4.1, implementation details: a cache block's score is the sum of its
+ *                                tokens' centralities
  *
  * Readings (the paper is silent or ambiguous): the window is the last w
  * positions n-w .. n-1 (the 1/w normaliser fixes w terms); by default every
@@ -216,4 +219,15 @@ void skv_oracle_gather_rows(const void* src, int64_t src_stride_head, int64_t sr
       memcpy((char*)dst + g * dst_stride_head + (dst_tok_base + i) * dst_stride_tok,
              (const char*)src + g * src_stride_head + (src_tok_base + idx[i]) * src_stride_tok,
              (size_t)row_bytes);
+}
+
+/* Block-level aggregation for paged caches (Sec. 4.1, implementation details): out[k] = sum of scores[k*block .. min(n,(k+1)*block)),
+ * k < ceil(n / block).  Plain left-to-right fp64 sums. */
+void skv_oracle_block_scores(const double* scores, int64_t n, int64_t block, double* out) {
+  const int64_t nb = (n + block - 1) / block;
+  for (int64_t k = 0; k < nb; ++k) {
+    double s = 0.0;
+    for (int64_t t = k * block; t < n && t < (k + 1) * block; ++t) s += scores[t];
+    out[k] = s;
+  }
 }

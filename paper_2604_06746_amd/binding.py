@@ -26,7 +26,7 @@ STRUCTKV_MAX_BATCH = 64
 EXPORTS = (
     "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
     "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_select_topk",
-    "structkv_gather_kv",
+    "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
     "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
 )
 
@@ -69,6 +69,10 @@ _lib.structkv_select_topk.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, 
 _lib.structkv_gather_kv.restype = _i32
 _lib.structkv_gather_kv.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp,
                                     _vp, _vp, _vp]
+_lib.structkv_truncate_hidden.restype = _i32
+_lib.structkv_truncate_hidden.argtypes = [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp]
+_lib.structkv_block_scores.restype = _i32
+_lib.structkv_block_scores.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
 _lib.structkv_debug_probs.restype = _i32
 _lib.structkv_debug_probs.argtypes = [_sp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
 _lib.structkv_debug_force_path.restype = _i32
@@ -185,6 +189,29 @@ def structkv_gather_kv(k_src: Optional[torch.Tensor], v_src: Optional[torch.Tens
                                    _ptr(v_dst), dst.stride(0), dst.stride(1), src.shape[0], src.shape[2],
                                    src.element_size(), len(rows_per_seq), cu, rows, _ptr(idx),
                                    _stream(stream)))
+
+
+def structkv_truncate_hidden(h_src: Optional[torch.Tensor], h_dst: Optional[torch.Tensor],
+                             pos_src: Optional[torch.Tensor], pos_dst: Optional[torch.Tensor],
+                             cu_seqlens: Sequence[int], rows_per_seq: Sequence[int], idx: torch.Tensor,
+                             stream=None) -> None:
+    """h_src [total, hidden], h_dst [rows, hidden] (last dim contiguous); pos_* int64 vectors or None."""
+    hidden = elem = ss = ds = 0
+    if h_src is not None:
+        assert h_src.dim() == 2 and h_src.stride(1) == 1 and h_dst.stride(1) == 1 and h_dst.dtype == h_src.dtype
+        hidden, elem, ss, ds = h_src.shape[1], h_src.element_size(), h_src.stride(0), h_dst.stride(0)
+    for p in (pos_src, pos_dst):
+        assert p is None or (p.dtype == torch.int64 and p.is_contiguous())
+    cu, rows = _host_i64(cu_seqlens), _host_i64(rows_per_seq)
+    _check(_lib.structkv_truncate_hidden(_ptr(h_src), ss, _ptr(h_dst), ds, hidden, elem, _ptr(pos_src),
+                                         _ptr(pos_dst), len(rows_per_seq), cu, rows, _ptr(idx), _stream(stream)))
+
+
+def structkv_block_scores(scores: torch.Tensor, cu_seqlens: Sequence[int], block_size: int,
+                          block_scores_out: torch.Tensor, stream=None) -> None:
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_block_scores(_ptr(scores), len(cu_seqlens) - 1, cu, block_size, _ptr(block_scores_out),
+                                      _stream(stream)))
 
 
 def structkv_debug_probs(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, n: int,

@@ -373,4 +373,66 @@ structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t
   return STRUCTKV_OK;
 }
 
+structkv_status structkv_truncate_hidden(const void* h_src, int64_t src_stride_tok, void* h_dst,
+                                         int64_t dst_stride_tok, int32_t hidden_dim, int32_t elem_bytes,
+                                         const int64_t* pos_src, int64_t* pos_dst, int32_t batch,
+                                         const int64_t* cu_seqlens, const int64_t* rows_per_seq,
+                                         const int32_t* idx, void* stream) {
+  // the hidden rows are one "head" of row gather; argument checks are shared with structkv_gather_kv
+  if (h_src || h_dst) {
+    structkv_status st = structkv_gather_kv(h_src, nullptr, 0, src_stride_tok, h_dst, nullptr, 0, dst_stride_tok, 1,
+                                            hidden_dim, elem_bytes, batch, cu_seqlens, rows_per_seq, idx, stream);
+    if (st != STRUCTKV_OK) return st;
+  } else {
+    clear_error();
+  }
+  if (!pos_dst) {
+    if (pos_src) return fail(STRUCTKV_ERR_INVALID_ARG, "pos_src given without pos_dst");
+    return STRUCTKV_OK;
+  }
+  SeqTable seq;
+  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (batch == 0) return STRUCTKV_OK;
+  if (!rows_per_seq) return fail(STRUCTKV_ERR_INVALID_ARG, "rows_per_seq is NULL");
+  int64_t out = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (rows_per_seq[b] < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "rows_per_seq[%d] < 0", b);
+    if (rows_per_seq[b] > 0 && seq.cu[b + 1] == seq.cu[b])
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d is empty but rows_per_seq is %lld", b,
+                  (long long)rows_per_seq[b]);
+    seq.out_off[b] = out;
+    out += rows_per_seq[b];
+  }
+  seq.out_off[batch] = out;
+  if (out == 0) return STRUCTKV_OK;
+  if (!idx) return fail(STRUCTKV_ERR_INVALID_ARG, "idx is NULL");
+  if (((uintptr_t)pos_src | (uintptr_t)pos_dst) & 7) return fail(STRUCTKV_ERR_INVALID_ARG, "positions not 8-byte aligned");
+  if (ceil_div(out, 256) >= ((int64_t)1 << 31)) return fail(STRUCTKV_ERR_UNSUPPORTED, "too many rows for one launch");
+  SKV_HIP_CHECK(launch_positions(pos_src, seq, idx, pos_dst, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_block_scores(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                      int32_t block_size, float* block_scores_out, void* stream) {
+  clear_error();
+  SeqTable seq;
+  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (block_size < 1) return fail(STRUCTKV_ERR_INVALID_ARG, "block_size must be >= 1");
+  if (batch == 0) return STRUCTKV_OK;
+  int64_t nb = 0;
+  for (int b = 0; b < batch; ++b) {
+    seq.out_off[b] = nb;
+    nb += ceil_div(seq.cu[b + 1] - seq.cu[b], block_size);
+  }
+  seq.out_off[batch] = nb;
+  if (nb == 0) return STRUCTKV_OK;
+  if (!scores || !block_scores_out) return fail(STRUCTKV_ERR_INVALID_ARG, "scores or block_scores_out is NULL");
+  if (((uintptr_t)scores | (uintptr_t)block_scores_out) & 3) return fail(STRUCTKV_ERR_INVALID_ARG, "pointers must be 4-byte aligned");
+  if (ceil_div(nb, 256) >= ((int64_t)1 << 31)) return fail(STRUCTKV_ERR_UNSUPPORTED, "too many blocks for one launch");
+  SKV_HIP_CHECK(launch_block_scores(scores, seq, block_size, block_scores_out, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
 }  // extern "C"

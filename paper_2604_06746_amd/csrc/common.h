@@ -66,6 +66,9 @@ hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, 
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);
 size_t topk_workspace_bytes(int batch, int64_t total_tokens);
+hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);
+hipError_t launch_positions(const int64_t* pos_src, const SeqTable& seq, const int32_t* idx, int64_t* pos_dst,
+                            hipStream_t st);
 hipError_t launch_gather(const void* k_src, const void* v_src, int64_t ssh, int64_t sst, void* k_dst,
                          void* v_dst, int64_t dsh, int64_t dst_, int G, int row_bytes,
                          const SeqTable& seq, const int32_t* idx, hipStream_t st);

@@ -112,6 +112,22 @@ def test_invalid_arguments_are_rejected_on_the_host(B):
     assert topk(fake, 1, cu, (i64 * 1)(10), 0, None, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert topk(fake, 1, cu, (i64 * 1)(0), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_OK   # nothing to do
 
+    blk = lib.structkv_block_scores
+    assert blk(fake, 1, cu, 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert blk(None, 1, cu, 16, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert blk(fake, 1, (i64 * 2)(0, -1), 16, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert blk(None, 1, (i64 * 2)(0, 0), 16, None, None) == B.STRUCTKV_OK
+
+    tr = lib.structkv_truncate_hidden
+    rows1 = (i64 * 1)(5)
+    assert tr(fake, 4096, None, 4096, 4096, 2, None, None, 1, cu, rows1, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert tr(fake, 64, fake, 4096, 4096, 2, None, None, 1, cu, rows1, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert tr(None, 0, None, 0, 0, 0, fake, None, 1, cu, rows1, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert tr(None, 0, None, 0, 0, 0, None, ctypes.c_void_p(4100), 1, cu, rows1, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert tr(None, 0, None, 0, 0, 0, None, fake, 1, cu, rows1, None, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert tr(None, 0, None, 0, 0, 0, None, None, 1, cu, rows1, fake, None) == B.STRUCTKV_OK      # nothing asked for
+    assert tr(None, 0, None, 0, 0, 0, None, fake, 1, cu, (i64 * 1)(0), fake, None) == B.STRUCTKV_OK
+
     gat = lib.structkv_gather_kv
     rows = (i64 * 1)(5)
     assert gat(fake, fake, 12800, 128, fake, fake, 640, 128, 8, 128, 3, 1, cu, rows, fake, None) == B.STRUCTKV_ERR_UNSUPPORTED

@@ -308,6 +308,79 @@ def test_gather_out_of_range_index_is_contained(B):
     assert torch.equal(kd[0, 0], k[0, 2]) and torch.equal(kd[0, 1], k[0, 0]) and torch.equal(kd[0, 2], k[0, 0])
 
 
+# ------------------------------------------------------------------ structural truncation (Eq. 11-12)
+
+@pytest.mark.parametrize("dtype,hidden", [(torch.bfloat16, 4096), (torch.float32, 520), (torch.bfloat16, 100)])
+def test_truncate_hidden_bit_exact(B, oracle, dtype, hidden):
+    rng = np.random.default_rng(hidden)
+    lens, ks = [700, 0, 1500], [60, 0, 333]
+    total = sum(lens)
+    h = torch.randn(total, hidden, device="cuda").to(dtype)
+    pos = torch.tensor(np.concatenate([rng.permutation(n) + 1000 * b for b, n in enumerate(lens)]),
+                       dtype=torch.int64, device="cuda")
+    idx = [np.sort(rng.choice(n, k, replace=False)).astype(np.int32) for n, k in zip(lens, ks)]
+    idx_d = torch.tensor(np.concatenate(idx), dtype=torch.int32, device="cuda")
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    rows = sum(ks)
+    h_ref, p_ref = oracle.truncate_hidden(to_oracle_array(h), pos.cpu().numpy(), idx, lens)
+    h_out = torch.zeros(rows, hidden, dtype=dtype, device="cuda")
+    p_out = torch.full((rows,), -1, dtype=torch.int64, device="cuda")
+    B.structkv_truncate_hidden(h, h_out, pos, p_out, cu, ks, idx_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_oracle_array(h_out), h_ref) and np.array_equal(p_out.cpu().numpy(), p_ref)
+    # identity positions: P' is the index list itself
+    _, p_ref0 = oracle.truncate_hidden(to_oracle_array(h), None, idx, lens)
+    p_out.fill_(-1)
+    B.structkv_truncate_hidden(None, None, None, p_out, cu, ks, idx_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(p_out.cpu().numpy(), p_ref0) and np.array_equal(p_ref0, np.concatenate(idx))
+    # a strided destination (rows of a wider buffer)
+    wide = torch.zeros(rows, hidden + 24, dtype=dtype, device="cuda")
+    B.structkv_truncate_hidden(h, wide[:, 8:8 + hidden], None, None, cu, ks, idx_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_oracle_array(wide[:, 8:8 + hidden].contiguous()), h_ref)
+    assert float(wide[:, :8].abs().sum()) == 0.0 and float(wide[:, 8 + hidden:].abs().sum()) == 0.0
+
+
+# ------------------------------------------------------------------ block-level aggregation (Sec. 4.1)
+
+@pytest.mark.parametrize("block", [1, 16, 100, 256])
+def test_block_scores_match_oracle(B, oracle, block):
+    rng = np.random.default_rng(block)
+    lens = [5000, 0, 37, 12288]
+    s = (rng.random(sum(lens)) ** 4).astype(np.float32)
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    ref = np.concatenate(oracle.block_scores(s, lens, block))
+    out = torch.full((len(ref),), -1.0, dtype=torch.float32, device="cuda")
+    B.structkv_block_scores(torch.tensor(s, device="cuda"), cu, block, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    # fp32 left-to-right sum of `block` non-negative terms: relative error below block * 2^-24
+    assert np.all(np.abs(got - ref) <= block * 2.0 ** -24 * ref + 1e-45)
+
+
+def test_block_selection_and_block_gather_compose(B, oracle):
+    # paged-cache eviction from block scores: keep the best blocks + the blocks of the window, move whole blocks
+    rng = np.random.default_rng(11)
+    G, n, d, bs = 2, 4096, 64, 16
+    nb, keep, tail = n // bs, 40, 2
+    c = (rng.random(n) ** 6).astype(np.float32)
+    k = torch.randn(G, n, d, device="cuda").to(torch.bfloat16)
+    sb = torch.empty(nb, dtype=torch.float32, device="cuda")
+    B.structkv_block_scores(torch.tensor(c, device="cuda"), [0, n], bs, sb)
+    idx = torch.empty(keep + tail, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.structkv_workspace_bytes(None, 1, nb), dtype=torch.uint8, device="cuda")
+    B.structkv_select_topk(sb, [0, nb], [keep], tail, idx, ws)
+    kd = torch.empty(G, keep + tail, bs * d, dtype=torch.bfloat16, device="cuda")
+    B.structkv_gather_kv(k.view(G, nb, bs * d), None, kd, None, [0, nb], [keep + tail], idx)
+    torch.cuda.synchronize()
+    ref_blocks = oracle.select_topk(sb.cpu().numpy(), [nb], [keep], tail)[0]
+    assert np.array_equal(idx.cpu().numpy(), ref_blocks)
+    tokens = (ref_blocks[:, None].astype(np.int64) * bs + np.arange(bs)[None, :]).reshape(-1).astype(np.int32)
+    ref_k = oracle.gather_kv(to_oracle_array(k), [tokens], [n])
+    assert np.array_equal(to_oracle_array(kd.view(G, (keep + tail) * bs, d)), ref_k)
+
+
 # ------------------------------------------------------------------ whole sweeps
 
 def test_tiny_config_full_sweep(sweep_mod, oracle):

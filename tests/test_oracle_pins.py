@@ -309,6 +309,41 @@ def test_gather_identity_and_fancy_index(oracle):
 
 # ------------------------------------------------------------------ the method's claim on planted structure
 
+def test_truncate_hidden_hand_values_and_identity(oracle):
+    # Eq. 11-12: rows and positions at the kept indices; two sequences, second offset by the first's length
+    h = (np.arange(7 * 3, dtype=np.float32).reshape(7, 3) * 0.5)
+    idx = [np.array([0, 2], np.int32), np.array([1, 3], np.int32)]
+    h2, p2 = oracle.truncate_hidden(h, None, idx, [3, 4])
+    assert np.array_equal(h2, h[[0, 2, 4, 6]]) and p2.tolist() == [0, 2, 1, 3]
+    pos = np.array([10, 11, 12, 100, 101, 102, 103], np.int64)
+    h3, p3 = oracle.truncate_hidden(h.view(np.uint32), pos, idx, [3, 4])
+    assert np.array_equal(h3.view(np.float32), h2) and p3.tolist() == [10, 12, 101, 103]
+    full = [np.arange(3, dtype=np.int32), np.arange(4, dtype=np.int32)]
+    h4, p4 = oracle.truncate_hidden(h, pos, full, [3, 4])
+    assert np.array_equal(h4, h) and np.array_equal(p4, pos)          # keeping everything changes nothing
+    bf = np.arange(5 * 6, dtype=np.uint16).reshape(5, 6)                # 2-byte elements, order reversed
+    h5, _ = oracle.truncate_hidden(bf, None, [np.array([4, 0], np.int32)], [5])
+    assert np.array_equal(h5, bf[[4, 0]])
+
+
+def test_block_scores_hand_values_and_invariants(oracle):
+    # Sec. 4.1 block-level aggregation: partial last block, per-sequence restart, mass conservation
+    s = np.array([1.0, 2.0, 4.0, 8.0, 16.0, 32.0, 64.0, 0.5, 0.25])
+    out = oracle.block_scores(s, [7, 2], 3)
+    assert out[0].tolist() == [7.0, 56.0, 64.0] and out[1].tolist() == [0.75]
+    rng = np.random.default_rng(5)
+    x = rng.random(1000)
+    for block in (1, 16, 64, 1000, 5000):
+        o = oracle.block_scores(x, [1000], block)[0]
+        assert len(o) == -(-1000 // block)
+        assert o.sum() == pytest.approx(x.sum(), rel=1e-13)
+        if block == 1:
+            assert np.array_equal(o, x)
+        if 1000 % block == 0:
+            assert np.allclose(o, x.reshape(-1, block).sum(1), rtol=1e-14, atol=0)
+    assert [len(o) for o in oracle.block_scores(np.zeros(5), [0, 5, 0], 4)] == [0, 2, 0]
+
+
 def test_planted_hubs_selected_by_centrality(oracle):
     # hubs that are dormant in half of the layers are missed by single-layer scores but kept by C
     wl = workloads.S_BF16
