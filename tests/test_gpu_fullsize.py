@@ -30,6 +30,27 @@ def test_full_size_layers(sweep_mod, oracle, name, layers):
     torch.cuda.empty_cache()
 
 
+def test_headline_config_whole_sweep(sweep_mod, oracle):
+    # every layer of the configuration bench.py times: D, entropy, C, per-layer top-k and gather against the
+    # oracle layer by layer, then the structural selection on the accumulated centrality
+    wl = workloads.C3_128K
+    sw, C = sweep_against_oracle(sweep_mod, oracle, wl, range(wl.n_layers), check_dormant=True)
+    sw.select_struct()
+    torch.cuda.synchronize()
+    got = sw.idx_struct.cpu().numpy()[:sw.rows]
+    c_gpu = sw.centrality.cpu().numpy()
+    assert np.array_equal(got, np.concatenate(oracle.select_topk(c_gpu, wl.seq_lens, wl.k_per_seq, wl.window)))
+    ref = oracle.select_topk(C, wl.seq_lens, wl.k_per_seq, wl.window)[0]
+    n, w, k = wl.seq_lens[0], wl.window, wl.k_per_seq[0]
+    tau = np.sort(C[:n - w])[::-1][k - 1]
+    for j in set(got.tolist()) ^ set(ref.tolist()):
+        assert abs(C[j] - tau) <= 1e-3 * abs(tau)
+    hubs = workloads.hub_positions(wl)[0]
+    ever = {p for i, p in enumerate(hubs) if any(workloads.hub_active(wl, l)[0][i] for l in range(wl.n_layers))}
+    assert ever and ever <= set(got.tolist())
+    torch.cuda.empty_cache()
+
+
 def test_million_token_layer(sweep_mod, oracle):
     wl = workloads.C4_1M
     sweep_against_oracle(sweep_mod, oracle, wl, (9,), check_dormant=True)
