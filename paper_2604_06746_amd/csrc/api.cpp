@@ -67,26 +67,44 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->R = gs * s.window;
   p->path = mfma_ok ? 0 : 1;
   if (p->path == 0) {
-    // MFMA kernels: one wave owns RPC = 32*RB <= 128 rows and KC keys; a KV group with more rows is cut into
-    // RC row-chunks, two per workgroup, whose waves share the key tiles
-    p->RB = p->R > 64 ? 4 : (p->R > 32 ? 2 : 1);
+    // MFMA kernels: one wave owns RPC = 32*RB rows and a chunk of KC keys.  A KV group with more than 128 rows
+    // (GQA 4 x w 64 = 256) is cut into row-chunks of 64 rows, four to a workgroup, whose waves share the key
+    // tiles; at 168 registers three such waves fit a SIMD, which hides more latency than two waves of 128 rows.
+    // Up to 128 rows: one wave per workgroup (128, 64 or 32 rows).
+    p->RB = p->R > 128 ? 2 : (p->R > 64 ? 4 : (p->R > 32 ? 2 : 1));
+    if (const char* e = getenv("STRUCTKV_DEBUG_RB")) {   // tuning knob: row blocks per wave
+      const long v = atol(e);
+      if (v == 1 || v == 2 || v == 4) p->RB = (int)v;
+    }
     p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
-    // keys per wave: about one full round of waves over the chip (two waves per SIMD) when the problem
-    // allows it, and at least 256 keys so that loading the query operands (RPC*d*2 bytes per wave) stays
-    // small against the K stream
-    int64_t kc = ceil_div(ceil_div(total * s.n_kv_heads * p->RC, 2048), 32) * 32;
+    p->NW = p->RC > 2 ? 4 : (p->RC > 1 ? 2 : 1);
+    if (const char* e = getenv("STRUCTKV_DEBUG_NW")) {   // tuning knob: waves per workgroup
+      const long v = atol(e);
+      if (v == 1 || v == 2 || v == 4) p->NW = (int)v;
+    }
+    // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave, 4 two-wave
+    // or 8 one-wave workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
+    // (RPC*d*2 bytes per wave) stays small against the K stream
+    const int64_t kMaxKC = p->NW == 4 ? 2048 : (p->NW == 2 ? 1024 : 896);   // the kernels' LDS column-sum capacity
+    const int64_t slots = 256 * (p->NW == 4 ? 3 : (p->NW == 2 ? 4 : 8));
+    const int64_t wg_per_chunk = s.n_kv_heads * ceil_div(p->RC, p->NW);
+    const int64_t chunks_per_round = slots / wg_per_chunk > 0 ? slots / wg_per_chunk : 1;
+    const int64_t rounds = ceil_div(total > 0 ? total : 1, chunks_per_round * kMaxKC);
+    int64_t kc = ceil_div(ceil_div(total, chunks_per_round * rounds), 32) * 32;
     if (kc < 256) kc = 256;
-    if (kc > 1024) kc = 1024;
+    if (kc > kMaxKC) kc = kMaxKC;
     if (const char* e = getenv("STRUCTKV_DEBUG_KC")) {   // tuning knob: keys per wave, multiple of 32, >= 256
       const long v = atol(e);
-      if (v >= 256 && v % 32 == 0) kc = v;
+      if (v >= 256 && v % 32 == 0 && v <= kMaxKC) kc = v;
     }
     p->KC = (int)kc;
+    p->CP = (int)ceil_div(p->RC, p->NW);
   } else {
-    p->RPC = 16; p->RB = 0; p->WK = 1;
+    p->RPC = 16; p->RB = 0; p->NW = 0; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
     p->KC = 256;
+    p->CP = p->RC;
   }
   if (seq) {
     p->n_chunks = 0;
@@ -99,7 +117,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->off_stats = off;   off += align_up(sizeof(float) * GRC * (size_t)p->n_chunks * p->WK * 3 * p->RPC, 256);
   p->off_lse = off;     off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads * s.window, 256);
   p->off_rowent = off;  off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads * s.window, 256);
-  p->off_colsum = off;  off += align_up(sizeof(float) * GRC * (size_t)total, 256);
+  p->off_colsum = off;  off += align_up(sizeof(float) * (size_t)s.n_kv_heads * p->CP * (size_t)total, 256);
   p->off_enthead = off; off += align_up(sizeof(float) * (size_t)batch * s.n_q_heads, 256);
   p->total_bytes = off;
 }

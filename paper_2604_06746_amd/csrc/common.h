@@ -42,6 +42,8 @@ struct ScorePlan {
   int KC;            // keys per key-chunk (one workgroup)
   int WK;            // partial statistics written per (row-chunk, key-chunk)
   int RB;            // MFMA path: 32-row blocks per wave (1, 2 or 4)
+  int NW;            // MFMA path: waves (row-chunks) per workgroup sharing the key tiles (1, 2 or 4)
+  int CP;            // pass-2 column-sum planes per KV head (the waves of a workgroup add theirs up first)
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
   // workspace carve (byte offsets)
   size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;

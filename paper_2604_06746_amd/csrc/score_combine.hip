@@ -206,11 +206,11 @@ hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, cons
   if (blocks == 0) blocks = 1;
   if (vec)
     hipLaunchKernelGGL(score_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                       s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
+                       s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
                        s.window, centrality, lambda, inv_w);
   else
     hipLaunchKernelGGL(score_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                       s.n_kv_heads * p.RC, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
+                       s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
                        s.window, centrality, lambda, inv_w);
   return hipGetLastError();
 }

@@ -51,9 +51,13 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// most keys a workgroup may be given (pass 2 keeps one fp32 column sum per key in LDS)
+// (one-wave workgroups: 896, so that eight of them -- 16 KB ring + 3.5 KB each -- still share a CU's 160 KB)
+template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896);
+
 // NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring
 template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP>
-__global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst,
     SeqTable seq, int Hq, int G, int w, int causal, float c2, int R, int RC, int KC, int64_t n_chunks,
     float* __restrict__ stats, const float* __restrict__ lse2, float* __restrict__ colsum,
@@ -67,6 +71,15 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
   constexpr int PD = NBUF - 1;             // tiles requested ahead of the one being consumed
   static_assert(NINST % NW == 0, "tile loads split evenly over the waves");
   __shared__ __attribute__((aligned(1024))) uint8_t ring[NBUF * TILE_BYTES];
+  // pass 2: the workgroup's column sums of its whole key chunk collect in LDS and are written out once at the
+  // end, so that the key loop holds no global store (a store between the tile loads would make the
+  // s_waitcnt vmcnt(N) below wait for younger loads than it has to).  With several waves, each wave parks
+  // its sums of tile s in csbuf[s % 3] and one wave adds them up, in wave order, two tiles later: by then
+  // every wave has waited for the LDS reads of tile s+1 (LDS operations complete in order, so its older
+  // csbuf write is done) and has passed the barrier of tile s+2 -- no extra wait, no extra barrier.
+  constexpr int KCAP = PASS == 2 ? kKeyCap<NW> : 1;
+  __shared__ float csout[KCAP];
+  __shared__ float csbuf[PASS == 2 && NW > 1 ? 3 : 1][PASS == 2 && NW > 1 ? NW : 1][PASS == 2 && NW > 1 ? 32 : 1];
   // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
   constexpr int VPM = PASS == 1 ? 8 : 4;
 
@@ -85,6 +98,7 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
   const int rc = live ? rc_raw : RC - 1;
   const int64_t chunk = t / rcg;
   const int grc = g * RC + rc;
+  const int plane = g * rcg + (int)(t % rcg);   // pass 2: the workgroup's column-sum plane
   int b = 0;
   while (b + 1 < seq.batch && chunk >= seq.chunk_start[b + 1]) ++b;
   const int64_t tok0 = seq.cu[b];
@@ -297,9 +311,20 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
     if (PASS == 2) {
       float cs = cs0 + cs1;
       cs += __shfl_xor(cs, 32);
-      const int j = jbase + l32;
-      if (live && lh == 0 && j < key_end) colsum[(int64_t)grc * total + tok0 + j] = cs;
+      if (lh == 0) {
+        if (NW == 1) csout[jbase - key0 + l32] = cs;
+        else         csbuf[((jbase - key0) >> 5) % 3][wave][l32] = live ? cs : 0.f;
+      }
       cs0 = 0.f; cs1 = 0.f;
+    }
+  };
+  // pass 2, several waves: add up the waves' sums of tile s_idx (see csbuf above for when this is safe)
+  auto flush_colsum = [&](int s_idx) __attribute__((always_inline)) {
+    if (PASS == 2 && NW > 1 && wave == (s_idx % NW) && lh == 0) {
+      float cs = csbuf[s_idx % 3][0][l32];
+#pragma unroll
+      for (int wv = 1; wv < NW; ++wv) cs += csbuf[s_idx % 3][wv][l32];
+      csout[32 * s_idx + l32] = cs;
     }
   };
   // prologue: request the first PD tiles
@@ -321,11 +346,23 @@ __global__ __launch_bounds__(64 * NW, 2) void score_mfma_ring_kernel(
     asm volatile("" ::: "memory");
     if (s + PD < nsub) issue_tile(s + PD);   // goes into the slot tile s-1 just left
     read_tile(s);
+    if (s >= 2) flush_colsum(s - 2);
     const int jbase = key0 + 32 * s;
     // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
     const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
     if (!masked) sub_tile(BoolC<false>{}, jbase);
     else         sub_tile(BoolC<true>{}, jbase);
+  }
+
+  if (PASS == 2) {
+    if (NW > 1) {
+      __syncthreads();
+      if (nsub >= 2) flush_colsum(nsub - 2);
+      if (nsub >= 1) flush_colsum(nsub - 1);
+    }
+    __syncthreads();
+    float* out = colsum + (int64_t)plane * total + tok0 + key0;
+    for (int i = threadIdx.x; i < key_end - key0; i += 64 * NW) out[i] = csout[i];
   }
 
   if (PASS == 1) {
@@ -375,9 +412,11 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
   // two waves (two row-chunks) per workgroup with a 4-tile ring when the KV group has more than 128 rows;
   // otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
 #define SKV_RING(d, nrb, nw, nbuf)                                                                      \
-  if (s.head_dim == d && p.RB == nrb && (p.RC > 1 ? 2 : 1) == nw)                                       \
+  if (s.head_dim == d && p.RB == nrb && p.NW == nw)                                                      \
     return launch_ring_cfg<d, nrb, nw, nbuf>(s, p, seq, q, k, ksh, kst, c2, stats, lse2, colsum, total, probs, pass, st)
   SKV_RING(128, 4, 2, 4);
+  SKV_RING(128, 2, 4, 4);
+  SKV_RING(128, 2, 2, 4);
   SKV_RING(128, 4, 1, 2);
   SKV_RING(128, 2, 1, 2);
   SKV_RING(128, 1, 1, 2);
