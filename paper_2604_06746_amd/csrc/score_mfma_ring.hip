@@ -420,6 +420,7 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
   SKV_RING(128, 4, 1, 2);
   SKV_RING(128, 2, 1, 2);
   SKV_RING(128, 1, 1, 2);
+  SKV_RING(64, 2, 4, 4);
   SKV_RING(64, 4, 2, 4);
   SKV_RING(64, 4, 1, 2);
   SKV_RING(64, 2, 1, 2);

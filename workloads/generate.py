@@ -125,6 +125,12 @@ S_BF16_W64 = _register(Workload("s_bf16_w64", 2, 8, 2, 128, (3001,), 64, "bf16",
 S_BF16_D64 = _register(Workload("s_bf16_d64", 2, 4, 4, 64, (1111,), 32, "bf16", (64,), 4, "all"))
 S_BF16_RAGGED = _register(Workload("s_bf16_ragged", 2, 8, 2, 128, (700, 33, 1500, 64), 32, "bf16",
                                    (35, 1, 75, 3), 2, "all"))
+# KV groups above 128 query rows that are not four full 64-row chunks: 3 x 64 = 192 rows (one idle wave),
+# 4 x 40 = 160 rows (a partly padded chunk), 8 x 64 = 512 rows (two workgroups per key chunk); d = 64 at 256 rows
+S_BF16_R192 = _register(Workload("s_bf16_r192", 2, 6, 2, 128, (1300, 90), 64, "bf16", (60, 4), 3, "all"))
+S_BF16_R160 = _register(Workload("s_bf16_r160", 2, 8, 2, 128, (999,), 40, "bf16", (50,), 3, "all"))
+S_BF16_R512 = _register(Workload("s_bf16_r512", 2, 16, 2, 128, (2100,), 64, "bf16", (100,), 3, "all"))
+S_BF16_D64_R256 = _register(Workload("s_bf16_d64_r256", 2, 8, 2, 64, (1500,), 64, "bf16", (70,), 3, "all"))
 S_F32_W8 = _register(Workload("s_f32_w8", 2, 4, 2, 64, (777,), 8, "f32", (50,), 3, "all"))
 S_F32_RAGGED = _register(Workload("s_f32_ragged", 2, 8, 8, 64, (300, 40, 513), 32, "f32", (15, 2, 25), 2, "all"))
 
