@@ -67,14 +67,15 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->R = gs * s.window;
   p->path = mfma_ok ? 0 : 1;
   if (p->path == 0) {
-    // MFMA kernels: one wave owns RPC = 32*RB rows and a chunk of KC keys.  A KV group with more than 128 rows
-    // (GQA 4 x w 64 = 256) is cut into row-chunks of 64 rows, four to a workgroup, whose waves share the key
-    // tiles; at 168 registers three such waves fit a SIMD, which hides more latency than two waves of 128 rows.
-    // Up to 128 rows: one wave per workgroup (128, 64 or 32 rows).
-    p->RB = p->R > 128 ? 2 : (p->R > 64 ? 4 : (p->R > 32 ? 2 : 1));
+    // MFMA kernels: one wave owns RPC = 32*RB <= 64 rows and a chunk of KC keys.  A KV group with more rows is
+    // cut into row-chunks of 64 rows whose waves form one workgroup and share the key tiles: four waves for more
+    // than 128 rows (GQA 4 x w 64 = 256; at 168 registers three such waves fit a SIMD), two waves for 65..128
+    // rows.  Waves of 64 rows beat waves of 128 rows (256 registers, two per SIMD) by 6 % at 256 rows and by
+    // 20-25 % at 128 rows: more waves hide more of the MFMA -> softmax latency.
+    p->RB = p->R > 32 ? 2 : 1;
     if (const char* e = getenv("STRUCTKV_DEBUG_RB")) {   // tuning knob: row blocks per wave
       const long v = atol(e);
-      if (v == 1 || v == 2 || v == 4) p->RB = (int)v;
+      if (v == 1 || v == 2) p->RB = (int)v;
     }
     p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);

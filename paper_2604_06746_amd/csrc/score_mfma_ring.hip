@@ -1,15 +1,17 @@
 // bf16 MFMA scoring kernels for gfx950 (paper Eq. 1, Eq. 2, Eq. 4): register-resident queries, keys
 // streamed HBM -> LDS by direct-to-LDS loads (no staging registers) through a ring of 32-key tiles.
 //
-// What shaped it (measured on MI355X): a ds_read_b128 stream sustains ~64 B/clk per CU, so an MFMA
-// (32 cycles per SIMD) fed from LDS must reuse each 1 KB operand read for at least 4 MFMAs; a single
-// wave cannot keep a SIMD's vector ALU busy (it issues an instruction every ~5-6 cycles, a
-// transcendental every ~20), so two waves per SIMD (<= 256 registers each) are needed; HBM latency
-// needs ~60 KB of unique loads in flight per CU.  Hence:
-//   * a wave owns a row-chunk of up to 128 query rows (4 blocks of 32) as MFMA operands in registers
-//     for the whole kernel, and reads each key operand from LDS ONCE per 32-key tile (4 MFMAs per read);
-//   * a KV group of 256 rows (GQA 4 x window 64) is two row-chunks = the two waves of a workgroup, which
-//     share the LDS tiles, so K crosses HBM -> L2 -> LDS once per pass;
+// What shaped it (measured on MI355X): under this mix of MFMA and vector work the chip runs at a
+// power-managed ~1.5 GHz and the vector ALU's issue port is the busiest unit (one vector instruction per
+// 4 cycles per SIMD, a transcendental ~2.6 of them); a single wave issues only every ~5-6 cycles, so
+// the port is fed by several waves per SIMD, and three waves of 64 query rows (168 registers) beat two
+// waves of 128 rows (256 registers); a ds_read_b128 stream sustains ~64 B/clk per CU, so each 1 KB
+// operand read from LDS must serve at least 2 MFMAs; HBM latency needs ~60 KB of loads in flight per CU.
+// Hence:
+//   * a wave owns a row-chunk of 64 query rows (2 blocks of 32; 32 rows for tiny KV groups) as MFMA
+//     operands in registers for the whole kernel, and reads each key operand from LDS once per 32-key tile;
+//   * a KV group of 256 rows (GQA 4 x window 64) is four row-chunks = the four waves of a workgroup (128
+//     rows: two waves), which share the LDS tiles, so K crosses HBM -> L2 -> LDS once per pass;
 //   * tiles are fetched with global_load_lds_dwordx4 (16 B per lane, lane L lands at base + 16 L), three
 //     tiles ahead, into an XOR-swizzled layout that makes the operand reads bank-conflict free;
 //   * inside a wave the MFMAs of row block rb+1 are issued under the softmax arithmetic of row block rb.
@@ -409,20 +411,17 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
                                   float* stats, const float* lse2, float* colsum, int64_t total,
                                   float* probs, int pass, hipStream_t st) {
   if (p.n_chunks == 0) return hipSuccess;
-  // two waves (two row-chunks) per workgroup with a 4-tile ring when the KV group has more than 128 rows;
-  // otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
+  // four or two waves (64-row row-chunks) per workgroup with a 4-tile ring when the KV group has more than
+  // 64 rows; otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
 #define SKV_RING(d, nrb, nw, nbuf)                                                                      \
   if (s.head_dim == d && p.RB == nrb && p.NW == nw)                                                      \
     return launch_ring_cfg<d, nrb, nw, nbuf>(s, p, seq, q, k, ksh, kst, c2, stats, lse2, colsum, total, probs, pass, st)
-  SKV_RING(128, 4, 2, 4);
   SKV_RING(128, 2, 4, 4);
   SKV_RING(128, 2, 2, 4);
-  SKV_RING(128, 4, 1, 2);
   SKV_RING(128, 2, 1, 2);
   SKV_RING(128, 1, 1, 2);
   SKV_RING(64, 2, 4, 4);
-  SKV_RING(64, 4, 2, 4);
-  SKV_RING(64, 4, 1, 2);
+  SKV_RING(64, 2, 2, 4);
   SKV_RING(64, 2, 1, 2);
   SKV_RING(64, 1, 1, 2);
 #undef SKV_RING
