@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 
 def parse_args():
@@ -152,7 +153,12 @@ def main():
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                     "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": round(kern_us[dom], 2)}
         score_us = sum(kern_us[k] for k in names[:4])
+        qk_flops = 2.0 * wl.n_q_heads * wl.window * wl.total_tokens * wl.head_dim      # Q_win K^T of one pass
         extra = {
+            "mfma": {"kernel": dom, "achieved_TFLOPs": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12, 1),
+                     "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                     "frac": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "flops_per_launch": qk_flops},
             "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
             "k_stream_both_passes": {"achieved_GBs": round(k_bytes / (score_us * 1e-6) / 1e9, 1),
                                      "frac": round(k_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
