@@ -60,6 +60,18 @@ structkv_status check_cu(int32_t batch, const int64_t* cu, SeqTable* seq) {
   return STRUCTKV_OK;
 }
 
+// Tuning knobs for kernel experiments, read from the environment once per process:
+// STRUCTKV_DEBUG_RB (32-row blocks per wave: 1, 2), STRUCTKV_DEBUG_NW (waves per workgroup: 1, 2, 4),
+// STRUCTKV_DEBUG_KC (keys per workgroup: a multiple of 32, at least 256).  Unset or invalid: the plan's own choice.
+struct TuningKnobs { long rb, nw, kc; };
+const TuningKnobs& tuning_knobs() {
+  static const TuningKnobs k = [] {
+    auto get = [](const char* name) { const char* e = getenv(name); return e ? atol(e) : 0L; };
+    return TuningKnobs{get("STRUCTKV_DEBUG_RB"), get("STRUCTKV_DEBUG_NW"), get("STRUCTKV_DEBUG_KC")};
+  }();
+  return k;
+}
+
 // Decide path, tiling and workspace layout.  `n_chunk_bound` < 0: exact from seq; otherwise an upper bound.
 void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t total, bool mfma_ok,
                ScorePlan* p) {
@@ -73,17 +85,12 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     // rows.  Waves of 64 rows beat waves of 128 rows (256 registers, two per SIMD) by 6 % at 256 rows and by
     // 20-25 % at 128 rows: more waves hide more of the MFMA -> softmax latency.
     p->RB = p->R > 32 ? 2 : 1;
-    if (const char* e = getenv("STRUCTKV_DEBUG_RB")) {   // tuning knob: row blocks per wave
-      const long v = atol(e);
-      if (v == 1 || v == 2) p->RB = (int)v;
-    }
+    const TuningKnobs& knobs = tuning_knobs();
+    if (knobs.rb == 1 || knobs.rb == 2) p->RB = (int)knobs.rb;
     p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
     p->NW = p->RC > 2 ? 4 : (p->RC > 1 ? 2 : 1);
-    if (const char* e = getenv("STRUCTKV_DEBUG_NW")) {   // tuning knob: waves per workgroup
-      const long v = atol(e);
-      if (v == 1 || v == 2 || v == 4) p->NW = (int)v;
-    }
+    if (knobs.nw == 1 || knobs.nw == 2 || knobs.nw == 4) p->NW = (int)knobs.nw;
     // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave, 4 two-wave
     // or 8 one-wave workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
     // (RPC*d*2 bytes per wave) stays small against the K stream
@@ -95,10 +102,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     int64_t kc = ceil_div(ceil_div(total, chunks_per_round * rounds), 32) * 32;
     if (kc < 256) kc = 256;
     if (kc > kMaxKC) kc = kMaxKC;
-    if (const char* e = getenv("STRUCTKV_DEBUG_KC")) {   // tuning knob: keys per wave, multiple of 32, >= 256
-      const long v = atol(e);
-      if (v >= 256 && v % 32 == 0 && v <= kMaxKC) kc = v;
-    }
+    if (knobs.kc >= 256 && knobs.kc % 32 == 0 && knobs.kc <= kMaxKC) kc = knobs.kc;
     p->KC = (int)kc;
     p->CP = (int)ceil_div(p->RC, p->NW);
   } else {

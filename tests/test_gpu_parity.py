@@ -416,6 +416,17 @@ def test_fused_score_accumulate_equals_two_calls(sweep_mod, name):
         assert torch.equal(two.entropy, one.entropy) and torch.equal(two.entropy_per_head, one.entropy_per_head)
 
 
+def test_batch_of_64_short_sequences(sweep_mod, oracle):
+    # the largest batch the ABI takes, ragged lengths from exactly one window up to a dozen key tiles
+    rng = np.random.default_rng(64)
+    lens = [int(x) for x in rng.integers(33, 400, 64)]
+    lens[5] = 32
+    lens[63] = 32
+    ks = [max(0, (n - 32) // 7) for n in lens]
+    wl = workloads.Workload("t_batch64", 2, 8, 2, 128, tuple(lens), 32, "bf16", tuple(ks), 0, "all")
+    sweep_against_oracle(sweep_mod, oracle, wl, range(2))
+
+
 def test_overlapped_sweep_equals_sequential(sweep_mod):
     # selection + gather of layer l on a side stream under the scoring of layer l+1: same bits as the plain loop
     wl = workloads.S_BF16_RAGGED
