@@ -112,6 +112,19 @@ structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, con
                                                 size_t workspace_bytes, void* stream);
 
 /*
+ * structkv_score_layer that also returns the in-degree per KV head (paper Eq. 2 before its outer sum
+ * over the KV groups):  indeg_groups_out[g][cu[b]+j] = sum_{h in H_g} sum_i a_{h,i,j},  [G][total] fp32,
+ * so that sum_g indeg_groups_out[g][t] = indeg_out[t] up to fp32 rounding.  For callers that keep one index
+ * set per KV head.  indeg_groups_out must be given whenever batch > 0.  Other arguments and outputs as
+ * structkv_score_layer.
+ */
+structkv_status structkv_score_layer_groups(const structkv_shape* shape, const void* q_win, const void* k,
+                                            int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                            const int64_t* cu_seqlens, float* indeg_out, float* indeg_groups_out,
+                                            float* entropy_out, float* entropy_per_head_out, void* workspace,
+                                            size_t workspace_bytes, void* stream);
+
+/*
  * Token selection (paper Eq. 10 on the centrality, Eq. 13 on a layer's scores): per sequence b the
  * k_b largest of scores[cu[b] .. cu[b+1]-keep_tail) -- ties go to the lower index -- united with the
  * last keep_tail positions (the observation window I_win).  Written in ascending order as

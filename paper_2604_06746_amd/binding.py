@@ -25,7 +25,8 @@ STRUCTKV_MAX_BATCH = 64
 
 EXPORTS = (
     "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
-    "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_select_topk",
+    "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_score_layer_groups",
+    "structkv_select_topk",
     "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
     "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
 )
@@ -64,6 +65,8 @@ _lib.structkv_accumulate_centrality.argtypes = [_vp, _vp, _i64, _f32, _f32, _vp]
 _lib.structkv_score_layer_accumulate.restype = _i32
 _lib.structkv_score_layer_accumulate.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _f32, _f32, _vp,
                                                  _vp, _vp, _sz, _vp]
+_lib.structkv_score_layer_groups.restype = _i32
+_lib.structkv_score_layer_groups.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.structkv_select_topk.restype = _i32
 _lib.structkv_select_topk.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.structkv_gather_kv.restype = _i32
@@ -165,6 +168,19 @@ def structkv_score_layer_accumulate(shape: structkv_shape, q_win: torch.Tensor, 
                                                 inv_w, _ptr(entropy_out), _ptr(entropy_per_head_out),
                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                 _stream(stream)))
+
+
+def structkv_score_layer_groups(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
+                                cu_seqlens: Sequence[int], indeg_out: torch.Tensor, indeg_groups_out: torch.Tensor,
+                                entropy_out: torch.Tensor, entropy_per_head_out: Optional[torch.Tensor],
+                                workspace: torch.Tensor, stream=None) -> None:
+    """indeg_groups_out: [G, total] fp32, contiguous."""
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous() and indeg_groups_out.is_contiguous()
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_score_layer_groups(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                            len(cu_seqlens) - 1, cu, _ptr(indeg_out), _ptr(indeg_groups_out),
+                                            _ptr(entropy_out), _ptr(entropy_per_head_out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def structkv_select_topk(scores: torch.Tensor, cu_seqlens: Sequence[int], k_per_seq: Sequence[int],

@@ -141,7 +141,7 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
                           int64_t kst, const SeqTable& seq_in, float* indeg, float* entropy,
                           float* ent_head_out, float* probs, void* ws, size_t ws_bytes, hipStream_t st,
                           int step_mask = 15, float* centrality = nullptr, float lambda = 0.f,
-                          float inv_w = 0.f) {
+                          float inv_w = 0.f, float* groups = nullptr) {
   const structkv_shape& s = *shape;
   SeqTable seq = seq_in;
   const int B = seq.batch;
@@ -175,6 +175,7 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   if (step_mask & 8)
     SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, centrality,
                                       lambda, inv_w, st));
+  if (groups) SKV_HIP_CHECK(launch_group_sums(s, p, colsum, total, groups, st));
   return STRUCTKV_OK;
 }
 
@@ -210,7 +211,7 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
                                         const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                         float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
                                         void* stream, int step_mask, float* centrality = nullptr,
-                                        float lambda = 0.f, float inv_w = 0.f) {
+                                        float lambda = 0.f, float inv_w = 0.f, float* groups = nullptr) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -234,7 +235,7 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg_out, entropy_out,
                    entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask,
-                   centrality, lambda, inv_w);
+                   centrality, lambda, inv_w, groups);
 }
 
 structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
@@ -262,6 +263,19 @@ structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, con
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
                           entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15, centrality,
                           lambda, inv_w);
+}
+
+structkv_status structkv_score_layer_groups(const structkv_shape* shape, const void* q_win, const void* k,
+                                            int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                            const int64_t* cu_seqlens, float* indeg_out, float* indeg_groups_out,
+                                            float* entropy_out, float* entropy_per_head_out, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (batch != 0 && (!indeg_groups_out || ((uintptr_t)indeg_groups_out & 3)))
+    return fail(STRUCTKV_ERR_INVALID_ARG, "indeg_groups_out is NULL or not 4-byte aligned");
+  return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15, nullptr, 0.f,
+                          0.f, indeg_groups_out);
 }
 
 structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,

@@ -64,6 +64,8 @@ hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, cons
                                const float* colsum, int64_t total, float* indeg, const float* row_ent,
                                float* ent_head, float* entropy, float* centrality, float lambda, float inv_w,
                                hipStream_t st);
+hipError_t launch_group_sums(const structkv_shape& s, const ScorePlan& p, const float* colsum, int64_t total,
+                             float* groups, hipStream_t st);
 hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st);
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);

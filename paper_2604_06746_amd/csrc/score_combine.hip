@@ -5,6 +5,7 @@
 //             plus the means over window rows and heads that finish Eq. 4; optionally also the
 //             centrality update below on the value it has just formed.
 //   accumulate : C <- lambda C + inv_w D   (Alg. 1 line 6 / Eq. 3).
+//   group sums : the same column sums per KV head only (Eq. 2's inner sum over h in H_g), on request.
 #include "common.h"
 
 namespace skv {
@@ -163,6 +164,17 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
   }
 }
 
+// per-KV-head in-degree: the column-sum planes of head g added up in plane order
+__global__ __launch_bounds__(256) void group_sums_kernel(const float* __restrict__ colsum, int CP, int64_t total,
+                                                         float* __restrict__ groups) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int g = blockIdx.y;
+  if (i >= total) return;
+  float a = 0.f;
+  for (int c = 0; c < CP; ++c) a += colsum[((int64_t)g * CP + c) * total + i];
+  groups[(int64_t)g * total + i] = a;
+}
+
 __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, const float* __restrict__ d,
                                                          int64_t n, float lambda, float inv_w, int vec) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -212,6 +224,14 @@ hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, cons
     hipLaunchKernelGGL(score_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
                        s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
                        s.window, centrality, lambda, inv_w);
+  return hipGetLastError();
+}
+
+hipError_t launch_group_sums(const structkv_shape& s, const ScorePlan& p, const float* colsum, int64_t total,
+                             float* groups, hipStream_t st) {
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)ceil_div(total, 256), (unsigned)s.n_kv_heads), dim3(256), 0,
+                     st, colsum, p.CP, total, groups);
   return hipGetLastError();
 }
 

@@ -102,6 +102,14 @@ def test_invalid_arguments_are_rejected_on_the_host(B):
     assert fused() == B.STRUCTKV_ERR_WORKSPACE            # everything else valid: stops at the NULL workspace
     assert fused(cen=None, batch=0) == B.STRUCTKV_OK
 
+    def groups(gout=fake, batch=1, ws=None):
+        return lib.structkv_score_layer_groups(ctypes.byref(ok_shape), fake, fake, 100 * 128, 128, batch, cu, fake,
+                                               gout, fake, None, ws, ws_bytes, None)
+    assert groups(gout=None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert groups(gout=ctypes.c_void_p(4097)) == B.STRUCTKV_ERR_INVALID_ARG
+    assert groups() == B.STRUCTKV_ERR_WORKSPACE           # everything else valid: stops at the NULL workspace
+    assert groups(gout=None, batch=0) == B.STRUCTKV_OK
+
     topk = lib.structkv_select_topk
     assert topk(fake, 1, cu, (i64 * 1)(101), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert topk(fake, 1, cu, (i64 * 1)(90), 32, fake, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG

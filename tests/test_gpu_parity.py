@@ -98,6 +98,32 @@ def test_score_layer_matches_oracle(B, sweep_mod, oracle, name, causal, force_si
         B.structkv_debug_force_path(prev)
 
 
+@pytest.mark.parametrize("name", ["s_bf16_w64", "s_bf16_gqa4", "s_bf16_r192", "s_f32_ragged"])
+def test_per_kv_head_indegree(B, sweep_mod, oracle, name):
+    # Eq. 2's inner sum only: per KV head, from the oracle's attention rows
+    wl = workloads.WORKLOADS[name]
+    sw = make_sweep(sweep_mod, wl)
+    x = workloads.make_layer(wl, 0, "cuda")
+    G, gs = wl.n_kv_heads, wl.n_q_heads // wl.n_kv_heads
+    groups = torch.full((G, wl.total_tokens), -3.0, dtype=torch.float32, device="cuda")
+    B.structkv_score_layer_groups(sw.shape, x.q_win, x.k, sw.cu, sw.indeg, groups, sw.entropy, sw.entropy_per_head,
+                                  sw.workspace)
+    torch.cuda.synchronize()
+    D, ent, _, probs = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads, G,
+                                          wl.head_dim, wl.window, wl.seq_lens, want_probs=True)
+    ref = np.concatenate([p.reshape(G, gs * wl.window, -1).sum(1) for p in probs], axis=1)
+    got = groups.cpu().numpy()
+    for g in range(G):
+        assert_close_floor(got[g], ref[g], _tol(wl), "group %d" % g)
+    assert_close_floor(sw.indeg.cpu().numpy(), D, _tol(wl), "indeg")
+    assert np.allclose(got.astype(np.float64).sum(0), sw.indeg.cpu().numpy(), rtol=1e-5, atol=1e-7)
+    # same call without the extra output: identical in-degree
+    keep = sw.indeg.clone()
+    sw.score(x.q_win, x.k)
+    torch.cuda.synchronize()
+    assert torch.equal(keep, sw.indeg)
+
+
 def test_score_layer_is_deterministic(sweep_mod):
     wl = workloads.S_BF16_RAGGED
     sw = make_sweep(sweep_mod, wl)
