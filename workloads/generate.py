@@ -131,6 +131,9 @@ S_BF16_R192 = _register(Workload("s_bf16_r192", 2, 6, 2, 128, (1300, 90), 64, "b
 S_BF16_R160 = _register(Workload("s_bf16_r160", 2, 8, 2, 128, (999,), 40, "bf16", (50,), 3, "all"))
 S_BF16_R512 = _register(Workload("s_bf16_r512", 2, 16, 2, 128, (2100,), 64, "bf16", (100,), 3, "all"))
 S_BF16_D64_R256 = _register(Workload("s_bf16_d64_r256", 2, 8, 2, 64, (1500,), 64, "bf16", (70,), 3, "all"))
+# small KV groups on the bf16 path: the paper's window of 8 (4 x 8 = 32 rows, one 32-row wave) and 64 rows
+S_BF16_W8 = _register(Workload("s_bf16_w8", 2, 8, 2, 128, (1234, 77), 8, "bf16", (60, 5), 3, "all"))
+S_BF16_R64 = _register(Workload("s_bf16_r64", 2, 4, 2, 128, (1800,), 32, "bf16", (90,), 3, "all"))
 S_F32_W8 = _register(Workload("s_f32_w8", 2, 4, 2, 64, (777,), 8, "f32", (50,), 3, "all"))
 S_F32_RAGGED = _register(Workload("s_f32_ragged", 2, 8, 8, 64, (300, 40, 513), 32, "f32", (15, 2, 25), 2, "all"))
 
