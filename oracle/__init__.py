@@ -49,6 +49,10 @@ def _load():
         lib.skv_oracle_gather_rows.argtypes = [vp, i64, i64, vp, i64, i64, i32, i64, vp, i64, i64, i64]
         lib.skv_oracle_block_scores.restype = None
         lib.skv_oracle_block_scores.argtypes = [vp, i64, i64, vp]
+        lib.skv_oracle_pivot_metrics.restype = None
+        lib.skv_oracle_pivot_metrics.argtypes = [vp, i32, i32, i64, f64, vp, vp]
+        lib.skv_oracle_transition.restype = i32
+        lib.skv_oracle_transition.argtypes = [vp, vp, vp, i32, f64, f64, f64, vp]
         _lib = lib
     return _lib
 
@@ -201,3 +205,38 @@ def block_scores(scores: np.ndarray, seq_lens: Sequence[int], block: int) -> Lis
         out.append(o)
         off += n
     return out
+
+
+def pivot_metrics(probs: Sequence[np.ndarray], top_frac: float = 0.1) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 5-6 per sequence from the attention rows score_layer(want_probs=True) returns ([Hq,w,n_b] each).
+
+    Reading: a head's attention is pooled (mean) over the window rows; sparsity = mass of its ceil(top_frac n)
+    largest keys, variance = population variance over the keys; both averaged over the heads.
+    Returns (sparsity [B], variance [B]) fp64.
+    """
+    lib = _load()
+    rho = np.zeros(len(probs))
+    var = np.zeros(len(probs))
+    for b, p in enumerate(probs):
+        p = np.ascontiguousarray(p, dtype=np.float64)
+        Hq, w, n = p.shape
+        if n == 0:
+            continue
+        r, v = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        lib.skv_oracle_pivot_metrics(_ptr(p), Hq, w, n, float(top_frac), ctypes.byref(r), ctypes.byref(v))
+        rho[b], var[b] = r.value, v.value
+    return rho, var
+
+
+def transition_scores(entropy: Sequence[float], sparsity: Sequence[float], variance: Sequence[float],
+                      weights: Sequence[float] = (0.2, 0.3, 0.5)) -> Tuple[np.ndarray, int]:
+    """Eq. 7-9 over the given layers: (T [L] with T[0] = 0, L* = argmax_l T_l + 1)."""
+    lib = _load()
+    H = np.ascontiguousarray(entropy, dtype=np.float64)
+    R = np.ascontiguousarray(sparsity, dtype=np.float64)
+    V = np.ascontiguousarray(variance, dtype=np.float64)
+    assert H.shape == R.shape == V.shape and H.ndim == 1
+    T = np.zeros(len(H))
+    ls = lib.skv_oracle_transition(_ptr(H), _ptr(R), _ptr(V), len(H), float(weights[0]), float(weights[1]),
+                                   float(weights[2]), _ptr(T))
+    return T, int(ls)

@@ -18,6 +18,9 @@
  *                                lower index, output ascending)
  *   skv_oracle_gather_rows       Alg. 1 line 17: keep K/V rows at the selected indices; the same row copy
  *                                serves Eq. 11 (hidden states and positions kept at I_struct)
+ *   skv_oracle_pivot_metrics     Eq. 5-6: sparsity (mass of the top 10 % of keys) and variance of a head's
+ *                                attention, read as the head's attention pooled (mean) over the window rows
+ *   skv_oracle_transition        Eq. 7-9: normalised metric gradients, transition score T_l, pivot layer L*
  *   skv_oracle_block_scores      Sec. 4.1, implementation details: a cache block's score is the sum of its
  *                                tokens' centralities
  *
@@ -230,4 +233,69 @@ void skv_oracle_block_scores(const double* scores, int64_t n, int64_t block, dou
     for (int64_t t = k * block; t < n && t < (k + 1) * block; ++t) s += scores[t];
     out[k] = s;
   }
+}
+
+/* Eq. 5-6.  The paper writes a^(l,h) with a free row index; reading: a^(l,h)_j = (1/w) sum_t a_{t,j}, the head's
+ * attention pooled over the window rows (a probability vector over the n keys).  Per head: rho_h = sum of its
+ * k = ceil(top_frac n) largest entries, var_h = (1/n) sum_j (a_j - mean)^2.  Outputs: means over the heads.
+ * probs: [Hq][w][n] attention rows of ONE sequence. */
+static int cmp_desc(const void* a, const void* b) {
+  const double x = *(const double*)a, y = *(const double*)b;
+  return x < y ? 1 : (x > y ? -1 : 0);
+}
+void skv_oracle_pivot_metrics(const double* probs, int Hq, int w, int64_t n, double top_frac, double* sparsity,
+                              double* variance) {
+  double rho = 0.0, var = 0.0;
+  double* pooled = (double*)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+  int64_t k = (int64_t)ceil(top_frac * (double)n);
+  if (k < 1) k = 1;
+  if (k > n) k = n;
+  for (int h = 0; h < Hq; ++h) {
+    double mean = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+      double s = 0.0;
+      for (int i = 0; i < w; ++i) s += probs[((int64_t)h * w + i) * n + j];
+      pooled[j] = s / w;
+      mean += pooled[j];
+    }
+    mean /= (double)n;
+    double v = 0.0;
+    for (int64_t j = 0; j < n; ++j) v += (pooled[j] - mean) * (pooled[j] - mean);
+    var += v / (double)n;
+    qsort(pooled, (size_t)n, sizeof(double), cmp_desc);
+    double top = 0.0;
+    for (int64_t j = 0; j < k; ++j) top += pooled[j];
+    rho += top;
+  }
+  free(pooled);
+  *sparsity = n > 0 ? rho / Hq : 0.0;
+  *variance = n > 0 ? var / Hq : 0.0;
+}
+
+/* Eq. 7-9 over the layers 0..L-1 given: dM_l = M_l - M_{l-1} for l >= 1, each metric's differences scaled to
+ * [0,1] over l = 1..L-1 (all equal: 0), T_l = w1 grad(-H)_l + w2 grad(rho)_l + w3 grad(V)_l, T_0 = 0 (no
+ * difference exists), L* = argmax_{l>=1} T_l + 1 (lowest l on ties; L < 2: returns L).  Returns L*. */
+int skv_oracle_transition(const double* H, const double* rho, const double* V, int L, double w1, double w2,
+                          double w3, double* T) {
+  for (int l = 0; l < L; ++l) T[l] = 0.0;
+  if (L < 2) return L;
+  const double* M[3] = {H, rho, V};
+  const double sign[3] = {-1.0, 1.0, 1.0};
+  const double wt[3] = {w1, w2, w3};
+  for (int m = 0; m < 3; ++m) {
+    double lo = 0.0, hi = 0.0;
+    for (int l = 1; l < L; ++l) {
+      const double d = sign[m] * (M[m][l] - M[m][l - 1]);
+      if (l == 1 || d < lo) lo = d;
+      if (l == 1 || d > hi) hi = d;
+    }
+    for (int l = 1; l < L; ++l) {
+      const double d = sign[m] * (M[m][l] - M[m][l - 1]);
+      T[l] += hi > lo ? wt[m] * (d - lo) / (hi - lo) : 0.0;
+    }
+  }
+  int best = 1;
+  for (int l = 2; l < L; ++l)
+    if (T[l] > T[best]) best = l;
+  return best + 1;
 }

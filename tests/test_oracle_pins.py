@@ -344,6 +344,60 @@ def test_block_scores_hand_values_and_invariants(oracle):
     assert [len(o) for o in oracle.block_scores(np.zeros(5), [0, 5, 0], 4)] == [0, 2, 0]
 
 
+def test_pivot_metrics_closed_forms(oracle):
+    # Eq. 5-6 on hand-made attention rows (probs [Hq][w][n])
+    n, w = 40, 2
+    uni = np.full((3, w, n), 1.0 / n)
+    rho, var = oracle.pivot_metrics([uni])
+    assert rho[0] == pytest.approx(4 / n, rel=1e-14) and var[0] == pytest.approx(0.0, abs=1e-30)   # k = ceil(0.1 n) = 4
+    one_hot = np.zeros((1, w, n)); one_hot[0, :, 7] = 1.0
+    rho, var = oracle.pivot_metrics([one_hot])
+    assert rho[0] == pytest.approx(1.0) and var[0] == pytest.approx((1 - 1 / n) / n, rel=1e-13)   # mean of (a-1/n)^2
+    # two rows that differ: the pooled vector is their mean; top-4 of n = 40
+    a = np.zeros((1, 2, n)); a[0, 0, :4] = 0.25; a[0, 1, 2:6] = 0.25
+    pooled = a[0].mean(0)
+    rho, var = oracle.pivot_metrics([a])
+    assert rho[0] == pytest.approx(np.sort(pooled)[::-1][:4].sum()) == pytest.approx(0.75)
+    assert var[0] == pytest.approx(pooled.var(), rel=1e-13)
+    # averaged over heads; ceil(0.1 n) with n = 41 is 5; an empty sequence gives zeros
+    both = np.concatenate([uni[:1], one_hot], axis=0)
+    rho, var = oracle.pivot_metrics([both, np.zeros((2, w, 0))])
+    assert rho[0] == pytest.approx((4 / n + 1.0) / 2) and rho[1] == 0.0 and var[1] == 0.0
+    u41 = np.full((1, 1, 41), 1 / 41)
+    assert oracle.pivot_metrics([u41])[0][0] == pytest.approx(5 / 41)
+    # from real rows: matches numpy on the oracle's own probabilities
+    wl = workloads.S_F32_W8
+    x = workloads.make_layer(wl, 0)
+    _, _, _, probs = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads, wl.n_kv_heads,
+                                        wl.head_dim, wl.window, wl.seq_lens, want_probs=True)
+    rho, var = oracle.pivot_metrics(probs)
+    pooled = probs[0].mean(1)
+    k = math.ceil(0.1 * pooled.shape[1])
+    assert rho[0] == pytest.approx(np.mean([np.sort(r)[::-1][:k].sum() for r in pooled]), rel=1e-12)
+    assert var[0] == pytest.approx(pooled.var(axis=1).mean(), rel=1e-12)
+
+
+def test_transition_scores_hand_values(oracle):
+    # Eq. 7-9: a sharp entropy drop with a rise in sparsity and variance between layers 2 and 3
+    H = [5.0, 4.9, 4.8, 2.0, 1.9]
+    rho = [0.2, 0.2, 0.25, 0.8, 0.8]
+    V = [1.0, 1.0, 1.5, 6.0, 6.5]
+    T, ls = oracle.transition_scores(H, rho, V, (0.2, 0.3, 0.5))
+    # differences: -H: .1 .1 2.8 .1 -> 0 0 1 0 ; rho: 0 .05 .55 0 -> 0 1/11 1 0 ; V: 0 .5 4.5 .5 -> 0 1/9 1 1/9
+    assert T.tolist() == pytest.approx([0.0, 0.0, 0.3 / 11 + 0.5 / 9, 1.0, 0.5 / 9])
+    assert ls == 4                                                     # argmax_l T_l + 1
+    T, ls = oracle.transition_scores([3.0, 3.0, 3.0], [0.1, 0.1, 0.1], [2.0, 2.0, 2.0])
+    assert T.tolist() == [0.0, 0.0, 0.0] and ls == 2                   # nothing moves: first candidate
+    T, ls = oracle.transition_scores([3.0, 2.0, 1.0], [0.125, 0.25, 0.375], [1.0, 2.0, 3.0])
+    assert T.tolist() == [0.0, 0.0, 0.0] and ls == 2                   # equal steps normalise to 0
+    T, ls = oracle.transition_scores([1.0, 0.5], [0.1, 0.4], [1.0, 1.0], (1.0, 1.0, 1.0))
+    assert ls == 2 and T.tolist() == [0.0, 0.0]                        # a single difference: max == min
+    assert oracle.transition_scores([1.0], [0.1], [1.0])[1] == 1
+    # weights only scale their own term
+    T, _ = oracle.transition_scores(H, rho, V, (1.0, 0.0, 0.0))
+    assert T.tolist() == pytest.approx([0.0, 0.0, 0.0, 1.0, 0.0])
+
+
 def test_planted_hubs_selected_by_centrality(oracle):
     # hubs that are dormant in half of the layers are missed by single-layer scores but kept by C
     wl = workloads.S_BF16
