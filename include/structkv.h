@@ -184,6 +184,37 @@ structkv_status structkv_block_scores(const float* scores, int32_t batch, const 
                                       int32_t block_size, float* block_scores_out, void* stream);
 
 /*
+ * Dynamic Pivot Layer Detection, the two metrics the scoring pass does not already produce (paper Eq. 5-6;
+ * the entropy of Eq. 4 comes from structkv_score_layer).  The paper leaves the row index of a^(l,h) free;
+ * here a head's attention is pooled over the window rows, a_h[j] = (1/w) sum_i a_{h,i,j}, a probability
+ * vector over the n_b keys of sequence b.  Per sequence:
+ *   sparsity_out[b] = (1/H_q) sum_h ( sum of the k largest a_h[j] ),   k = ceil(top_frac * n_b) in double arithmetic (paper: 0.1)
+ *   variance_out[b] = (1/H_q) sum_h (1/n_b) sum_j (a_h[j] - 1/n_b)^2
+ * (0 for an empty sequence).  It re-scores the layer head by head through the same kernels, so it costs about
+ * as much as scoring the layer twice; call it only on the layers where the detector is still running.
+ * q_win, k, strides, cu_seqlens, shape: as structkv_score_layer.  sparsity_out, variance_out: DEVICE fp32 [B].
+ * workspace: structkv_pivot_workspace_bytes(shape, longest sequence) bytes, 256-byte aligned.
+ */
+size_t structkv_pivot_workspace_bytes(const structkv_shape* shape, int64_t max_seq_len);
+structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* q_win, const void* k,
+                                       int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                       const int64_t* cu_seqlens, double top_frac, float* sparsity_out,
+                                       float* variance_out, void* workspace, size_t workspace_bytes,
+                                       void* stream);
+
+/*
+ * Transition score and pivot layer (paper Eq. 7-9), HOST arithmetic on HOST arrays of per-layer metrics
+ * (layers 0 .. n_layers-1 of the un-pruned prefix):  dM_l = M_l - M_{l-1} for l >= 1; each metric's differences
+ * are min-max scaled to [0,1] over l = 1 .. n_layers-1 (a metric whose differences are all equal contributes 0);
+ *   t_out[l] = w1 * grad(-entropy)_l + w2 * grad(sparsity)_l + w3 * grad(variance)_l,   t_out[0] = 0;
+ *   *pivot_layer_out = argmax_{l >= 1} t_out[l] + 1   (lowest l on ties; n_layers < 2: n_layers).
+ * The paper's weights are (0.2, 0.3, 0.5).
+ */
+structkv_status structkv_transition_scores(const double* entropy, const double* sparsity, const double* variance,
+                                           int32_t n_layers, double w1, double w2, double w3, double* t_out,
+                                           int32_t* pivot_layer_out);
+
+/*
  * Test hook: the attention rows themselves (paper Eq. 1) for ONE sequence of n tokens,
  * probs_out [H_q][w][n] fp32, computed by the same kernels as structkv_score_layer.
  * H_q*w*n must not exceed 2^26.

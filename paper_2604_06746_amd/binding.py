@@ -28,6 +28,7 @@ EXPORTS = (
     "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_score_layer_groups",
     "structkv_select_topk",
     "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
+    "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_transition_scores",
     "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
 )
 
@@ -76,6 +77,14 @@ _lib.structkv_truncate_hidden.restype = _i32
 _lib.structkv_truncate_hidden.argtypes = [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp]
 _lib.structkv_block_scores.restype = _i32
 _lib.structkv_block_scores.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
+_lib.structkv_pivot_workspace_bytes.restype = _sz
+_lib.structkv_pivot_workspace_bytes.argtypes = [_sp, _i64]
+_lib.structkv_pivot_metrics.restype = _i32
+_lib.structkv_pivot_metrics.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, ctypes.c_double, _vp, _vp, _vp, _sz,
+                                        _vp]
+_lib.structkv_transition_scores.restype = _i32
+_lib.structkv_transition_scores.argtypes = [_vp, _vp, _vp, _i32, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                            _vp, _vp]
 _lib.structkv_debug_probs.restype = _i32
 _lib.structkv_debug_probs.argtypes = [_sp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
 _lib.structkv_debug_force_path.restype = _i32
@@ -228,6 +237,33 @@ def structkv_block_scores(scores: torch.Tensor, cu_seqlens: Sequence[int], block
     cu = _host_i64(cu_seqlens)
     _check(_lib.structkv_block_scores(_ptr(scores), len(cu_seqlens) - 1, cu, block_size, _ptr(block_scores_out),
                                       _stream(stream)))
+
+
+def structkv_pivot_workspace_bytes(shape: structkv_shape, max_seq_len: int) -> int:
+    return int(_lib.structkv_pivot_workspace_bytes(ctypes.byref(shape), int(max_seq_len)))
+
+
+def structkv_pivot_metrics(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, cu_seqlens: Sequence[int],
+                           top_frac: float, sparsity_out: torch.Tensor, variance_out: torch.Tensor,
+                           workspace: torch.Tensor, stream=None) -> None:
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous()
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_pivot_metrics(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                       len(cu_seqlens) - 1, cu, top_frac, _ptr(sparsity_out), _ptr(variance_out),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _stream(stream)))
+
+
+def structkv_transition_scores(entropy: Sequence[float], sparsity: Sequence[float], variance: Sequence[float],
+                               weights: Sequence[float] = (0.2, 0.3, 0.5)):
+    """Host arithmetic (Eq. 7-9): returns (list of T_l, pivot layer L*)."""
+    n = len(entropy)
+    assert len(sparsity) == n and len(variance) == n
+    arr = ctypes.c_double * max(n, 1)
+    H, R, V, T = arr(*entropy), arr(*sparsity), arr(*variance), arr()
+    ls = ctypes.c_int32(0)
+    _check(_lib.structkv_transition_scores(H, R, V, n, weights[0], weights[1], weights[2], T, ctypes.byref(ls)))
+    return list(T)[:n], int(ls.value)
 
 
 def structkv_debug_probs(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, n: int,

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstructkv.so")
 SOURCES = ["api.cpp", "score_mfma_ring.hip", "score_simt.hip", "score_combine.hip", "topk.hip", "gather.hip",
-           "aggregate.hip"]
+           "aggregate.hip", "pivot.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-x", "hip",
          # packed-fp32 instruction selection is switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -472,4 +472,150 @@ structkv_status structkv_block_scores(const float* scores, int32_t batch, const 
   return STRUCTKV_OK;
 }
 
+// ---- Dynamic Pivot Layer Detection: metrics (Eq. 5-6) and transition score (Eq. 7-9) --------------------------
+
+namespace {
+struct PivotCarve {
+  size_t off_heads, off_indeg, off_idx, off_small, off_score_ws, off_topk_ws, total;
+  size_t score_ws_bytes, topk_ws_bytes;
+};
+// scratch for ONE sequence of at most n_max tokens at a time (sequences are processed one after the other)
+bool pivot_carve(const structkv_shape& s, int64_t n_max, structkv_shape* sub, PivotCarve* c) {
+  const int gs = s.n_q_heads / s.n_kv_heads;
+  *sub = s;
+  sub->n_q_heads = gs;      // the gs query heads of one KV head, each as a group of its own
+  sub->n_kv_heads = gs;
+  const int hb = s.n_q_heads < kMaxBatch ? s.n_q_heads : kMaxBatch;   // heads per top-k call
+  const size_t N = (size_t)(n_max > 0 ? n_max : 1);
+  c->score_ws_bytes = structkv_workspace_bytes(sub, 1, n_max);
+  c->topk_ws_bytes = structkv_workspace_bytes(nullptr, hb, (int64_t)hb * n_max);
+  if (c->score_ws_bytes == 0 || c->topk_ws_bytes == 0) return false;
+  size_t off = 0;
+  c->off_heads = off;     off += align_up(sizeof(float) * (size_t)s.n_q_heads * N, 256);
+  c->off_indeg = off;     off += align_up(sizeof(float) * N, 256);
+  c->off_idx = off;       off += align_up(sizeof(int32_t) * (size_t)s.n_q_heads * N, 256);
+  c->off_small = off;     off += align_up(sizeof(float) * (size_t)(3 * s.n_q_heads + 8), 256);
+  c->off_score_ws = off;  off += align_up(c->score_ws_bytes, 256);
+  c->off_topk_ws = off;   off += align_up(c->topk_ws_bytes, 256);
+  c->total = off;
+  return true;
+}
+}  // namespace
+
+size_t structkv_pivot_workspace_bytes(const structkv_shape* shape, int64_t max_seq_len) {
+  if (!shape || check_shape(shape) != STRUCTKV_OK || max_seq_len < 0) return 0;
+  structkv_shape sub;
+  PivotCarve c;
+  if (!pivot_carve(*shape, max_seq_len, &sub, &c)) return 0;
+  return c.total;
+}
+
+structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* q_win, const void* k,
+                                       int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                       const int64_t* cu_seqlens, double top_frac, float* sparsity_out,
+                                       float* variance_out, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  structkv_status st = check_shape(shape);
+  if (st != STRUCTKV_OK) return st;
+  SeqTable seq;
+  st = check_cu(batch, cu_seqlens, &seq);
+  if (st != STRUCTKV_OK) return st;
+  if (!(top_frac > 0.0 && top_frac <= 1.0)) return fail(STRUCTKV_ERR_INVALID_ARG, "top_frac must be in (0,1]");
+  if (batch == 0) return STRUCTKV_OK;
+  if (!q_win || !sparsity_out || !variance_out) return fail(STRUCTKV_ERR_INVALID_ARG, "NULL pointer");
+  const int64_t total = seq.cu[batch];
+  if (total > 0 && !k) return fail(STRUCTKV_ERR_INVALID_ARG, "k is NULL");
+  if (k_stride_tok < shape->head_dim) return fail(STRUCTKV_ERR_INVALID_ARG, "k_stride_tok < head_dim");
+  if (shape->n_kv_heads > 1 && k_stride_head < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "k_stride_head < 0");
+  int64_t n_max = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    if (n > n_max) n_max = n;
+    if (n >= ((int64_t)1 << 31)) return fail(STRUCTKV_ERR_UNSUPPORTED, "sequence %d is too long", b);
+    if (shape->causal && n != 0 && n < shape->window)
+      return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: causal scoring needs n >= window", b);
+  }
+  if (!workspace || ((uintptr_t)workspace & 255))
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  structkv_shape sub;
+  PivotCarve c;
+  if (!pivot_carve(*shape, n_max, &sub, &c)) return fail(STRUCTKV_ERR_UNSUPPORTED, "cannot size the scratch");
+  if (workspace_bytes < c.total)
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, pivot metrics need %zu", workspace_bytes, c.total);
+
+  uint8_t* w8 = (uint8_t*)workspace;
+  float* heads = (float*)(w8 + c.off_heads);
+  float* indeg = (float*)(w8 + c.off_indeg);
+  int32_t* idx = (int32_t*)(w8 + c.off_idx);
+  float* rho_h = (float*)(w8 + c.off_small);
+  float* var_h = rho_h + shape->n_q_heads;
+  float* ent = var_h + shape->n_q_heads;           // entropy outputs of the sub-calls: not used here
+  float* ent_h = ent + 4;
+  const int Hq = shape->n_q_heads, G = shape->n_kv_heads, gs = Hq / G, w = shape->window, d = shape->head_dim;
+  const size_t e = shape->dtype == STRUCTKV_DTYPE_BF16 ? 2 : 4;
+  hipStream_t hs = (hipStream_t)stream;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    if (n > 0) {
+      // per-head in-degree D_h [Hq][n]: the gs heads of KV head g scored as gs groups that share one K head
+      const int64_t cu1[2] = {0, n};
+      for (int g = 0; g < G; ++g) {
+        const uint8_t* qs = (const uint8_t*)q_win + ((size_t)b * Hq + (size_t)g * gs) * w * d * e;
+        const uint8_t* ks = (const uint8_t*)k + ((size_t)g * k_stride_head + (size_t)seq.cu[b] * k_stride_tok) * e;
+        st = score_layer_impl(&sub, qs, ks, 0, k_stride_tok, 1, cu1, indeg, ent, ent_h, w8 + c.off_score_ws,
+                              c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads + (size_t)g * gs * n);
+        if (st != STRUCTKV_OK) return st;
+      }
+      // the ceil(top_frac n) largest keys of every head: heads are the "sequences" of one selection call
+      int64_t kk = (int64_t)std::ceil(top_frac * (double)n);
+      if (kk < 1) kk = 1;
+      if (kk > n) kk = n;
+      for (int h0 = 0; h0 < Hq; h0 += kMaxBatch) {
+        const int hb = Hq - h0 < kMaxBatch ? Hq - h0 : kMaxBatch;
+        int64_t cuh[kMaxBatch + 1], kh[kMaxBatch];
+        for (int i = 0; i <= hb; ++i) cuh[i] = (int64_t)i * n;
+        for (int i = 0; i < hb; ++i) kh[i] = kk;
+        st = structkv_select_topk(heads + (size_t)h0 * n, hb, cuh, kh, 0, idx + (size_t)h0 * kk,
+                                  w8 + c.off_topk_ws, c.topk_ws_bytes, stream);
+        if (st != STRUCTKV_OK) return st;
+      }
+      SKV_HIP_CHECK(launch_pivot_heads(heads, Hq, n, idx, kk, 1.0f / (float)w, rho_h, var_h, hs));
+    }
+    SKV_HIP_CHECK(launch_pivot_finish(rho_h, var_h, Hq, n > 0 ? 1 : 0, sparsity_out + b, variance_out + b, hs));
+  }
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_transition_scores(const double* entropy, const double* sparsity, const double* variance,
+                                           int32_t n_layers, double w1, double w2, double w3, double* t_out,
+                                           int32_t* pivot_layer_out) {
+  clear_error();
+  if (n_layers < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "n_layers < 0");
+  if (n_layers > 0 && (!entropy || !sparsity || !variance || !t_out))
+    return fail(STRUCTKV_ERR_INVALID_ARG, "NULL pointer");
+  if (!pivot_layer_out) return fail(STRUCTKV_ERR_INVALID_ARG, "pivot_layer_out is NULL");
+  for (int l = 0; l < n_layers; ++l) t_out[l] = 0.0;
+  if (n_layers < 2) { *pivot_layer_out = n_layers; return STRUCTKV_OK; }
+  const double* metric[3] = {entropy, sparsity, variance};
+  const double sign[3] = {-1.0, 1.0, 1.0};   // a DROP in entropy, a RISE in sparsity and variance
+  const double weight[3] = {w1, w2, w3};
+  for (int m = 0; m < 3; ++m) {
+    // first differences, then min-max scaling over the layers that have one
+    double lo = sign[m] * (metric[m][1] - metric[m][0]), hi = lo;
+    for (int l = 2; l < n_layers; ++l) {
+      const double dl = sign[m] * (metric[m][l] - metric[m][l - 1]);
+      lo = dl < lo ? dl : lo;
+      hi = dl > hi ? dl : hi;
+    }
+    if (!(hi > lo)) continue;
+    for (int l = 1; l < n_layers; ++l)
+      t_out[l] += weight[m] * (sign[m] * (metric[m][l] - metric[m][l - 1]) - lo) / (hi - lo);
+  }
+  int best = 1;
+  for (int l = 2; l < n_layers; ++l)
+    if (t_out[l] > t_out[best]) best = l;
+  *pivot_layer_out = best + 1;
+  return STRUCTKV_OK;
+}
+
 }  // extern "C"

@@ -70,6 +70,10 @@ hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, 
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);
 size_t topk_workspace_bytes(int batch, int64_t total_tokens);
+hipError_t launch_pivot_heads(const float* heads, int H, int64_t n, const int32_t* idx, int64_t k, float inv_w,
+                              float* rho_h, float* var_h, hipStream_t st);
+hipError_t launch_pivot_finish(const float* rho_h, const float* var_h, int H, int valid, float* sparsity,
+                               float* variance, hipStream_t st);
 hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);
 hipError_t launch_positions(const int64_t* pos_src, const SeqTable& seq, const int32_t* idx, int64_t* pos_dst,
                             hipStream_t st);

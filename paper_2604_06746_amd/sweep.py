@@ -61,6 +61,18 @@ class LayerSweep:
         B.structkv_score_layer_accumulate(self.shape, q_win, k, self.cu, self.indeg, self.centrality, self.lam,
                                           1.0 / self.w, self.entropy, self.entropy_per_head, self.workspace, stream)
 
+    def pivot_metrics(self, q_win: torch.Tensor, k: torch.Tensor, top_frac: float = 0.1, stream=None):
+        """Eq. 5-6 for this layer: (sparsity [B], variance [B]) device tensors; the entropy of Eq. 4 is self.entropy
+        after score().  Allocates its scratch on first use."""
+        if getattr(self, "_pivot_ws", None) is None:
+            nbytes = B.structkv_pivot_workspace_bytes(self.shape, max(self.seq_lens) if self.seq_lens else 0)
+            self._pivot_ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.centrality.device)
+            self.sparsity = torch.zeros(max(self.batch, 1), dtype=torch.float32, device=self.centrality.device)
+            self.variance = torch.zeros_like(self.sparsity)
+        B.structkv_pivot_metrics(self.shape, q_win, k, self.cu, top_frac, self.sparsity, self.variance,
+                                 self._pivot_ws, stream)
+        return self.sparsity, self.variance
+
     def select_kv(self, stream=None) -> None:
         """Eq. 13: per-layer storage indices from this layer's scores."""
         B.structkv_select_topk(self.indeg, self.cu, self.k_per_seq, self.keep_tail, self.idx_kv,

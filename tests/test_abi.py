@@ -1,6 +1,8 @@
 """CPU-only checks of the C ABI: the library loads, exports what the header declares, and rejects
 bad arguments before touching the GPU."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -155,3 +157,42 @@ def test_binding_raises_with_message(B):
     with pytest.raises(B.StructKVError) as e:
         B.structkv_score_layer(s, q, k, [0, 100], out, out, None, out, stream=0)
     assert e.value.status == B.STRUCTKV_ERR_INVALID_ARG and "divide" in str(e.value)
+
+
+def test_transition_scores_match_the_oracle(B, oracle):
+    # Eq. 7-9 is host arithmetic in the library: hand values and random metric curves against the oracle
+    T, ls = B.structkv_transition_scores([5.0, 4.9, 4.8, 2.0, 1.9], [0.2, 0.2, 0.25, 0.8, 0.8],
+                                         [1.0, 1.0, 1.5, 6.0, 6.5], (0.2, 0.3, 0.5))
+    assert T == pytest.approx([0.0, 0.0, 0.3 / 11 + 0.5 / 9, 1.0, 0.5 / 9]) and ls == 4
+    rng = np.random.default_rng(9)
+    for L in (1, 2, 3, 8, 32, 80):
+        H, R, V = rng.random(L) * 6, rng.random(L), rng.random(L) * 1e-9
+        T, ls = B.structkv_transition_scores(H.tolist(), R.tolist(), V.tolist())
+        Tr, lr = oracle.transition_scores(H, R, V)
+        assert ls == lr and np.allclose(T, Tr, rtol=1e-13, atol=0)
+    T, ls = B.structkv_transition_scores([], [], [])
+    assert T == [] and ls == 0
+    T, ls = B.structkv_transition_scores([3.0, 3.0, 3.0], [0.5, 0.5, 0.5], [1.0, 1.0, 1.0])
+    assert T == [0.0, 0.0, 0.0] and ls == 2
+
+
+def test_pivot_metrics_arguments(B):
+    lib = B._lib
+    i64 = ctypes.c_int64
+    cu = (i64 * 2)(0, 100)
+    fake = ctypes.c_void_p(4096)
+    shape = B.make_shape(8, 2, 128, 32, B.STRUCTKV_DTYPE_BF16)
+    need = B.structkv_pivot_workspace_bytes(shape, 100)
+    assert need > 0 and need % 256 == 0
+    assert B.structkv_pivot_workspace_bytes(shape, 1 << 20) > B.structkv_pivot_workspace_bytes(shape, 1 << 10)
+    assert B.structkv_pivot_workspace_bytes(B.make_shape(8, 3, 128, 32, 1), 100) == 0
+
+    def call(frac=0.1, sp=fake, ws=fake, wsb=need, batch=1):
+        return lib.structkv_pivot_metrics(ctypes.byref(shape), fake, fake, 100 * 128, 128, batch, cu, float(frac), sp, fake, ws,
+                                          wsb, None)
+    assert call(frac=0.0) == B.STRUCTKV_ERR_INVALID_ARG
+    assert call(frac=1.5) == B.STRUCTKV_ERR_INVALID_ARG
+    assert call(sp=None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert call(ws=None) == B.STRUCTKV_ERR_WORKSPACE
+    assert call(wsb=need - 256) == B.STRUCTKV_ERR_WORKSPACE and "need" in B.structkv_last_error()
+    assert call(batch=0) == B.STRUCTKV_OK

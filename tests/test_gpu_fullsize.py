@@ -51,6 +51,27 @@ def test_headline_config_whole_sweep(sweep_mod, oracle):
     torch.cuda.empty_cache()
 
 
+def test_pivot_metrics_at_32k(sweep_mod, oracle):
+    # Eq. 5-6 on one layer of the 32K configuration against the oracle's attention rows (268 MB of fp64)
+    from paper_2604_06746_amd import binding as B
+    from helpers import make_sweep, to_oracle_array
+    wl = workloads.C2_32K
+    sw = make_sweep(sweep_mod, wl)
+    x = workloads.make_layer(wl, 7, "cuda")
+    ws = torch.empty(B.structkv_pivot_workspace_bytes(sw.shape, wl.seq_lens[0]), dtype=torch.uint8, device="cuda")
+    rho = torch.zeros(1, device="cuda")
+    var = torch.zeros(1, device="cuda")
+    B.structkv_pivot_metrics(sw.shape, x.q_win, x.k, sw.cu, 0.1, rho, var, ws)
+    torch.cuda.synchronize()
+    _, _, _, probs = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads, wl.n_kv_heads,
+                                        wl.head_dim, wl.window, wl.seq_lens, want_probs=True)
+    rho_ref, var_ref = oracle.pivot_metrics(probs, 0.1)
+    assert abs(rho.item() - rho_ref[0]) <= 1e-3 * rho_ref[0]
+    assert abs(var.item() - var_ref[0]) <= 2e-3 * var_ref[0]
+    del ws
+    torch.cuda.empty_cache()
+
+
 def test_million_token_layer(sweep_mod, oracle):
     wl = workloads.C4_1M
     sweep_against_oracle(sweep_mod, oracle, wl, (9,), check_dormant=True)

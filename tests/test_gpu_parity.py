@@ -408,6 +408,76 @@ def test_block_selection_and_block_gather_compose(B, oracle):
     assert np.array_equal(to_oracle_array(kd.view(G, (keep + tail) * bs, d)), ref_k)
 
 
+# ------------------------------------------------------------------ pivot metrics (Eq. 5-6)
+
+@pytest.mark.parametrize("name,causal", [("s_bf16_w64", False), ("s_bf16_ragged", False), ("s_bf16_ragged", True),
+                                         ("s_bf16_w8", False), ("s_f32_ragged", False), ("c1_tiny", False)])
+def test_pivot_metrics_match_oracle(B, sweep_mod, oracle, name, causal):
+    wl = workloads.WORKLOADS[name]
+    sw = make_sweep(sweep_mod, wl, causal)
+    x = workloads.make_layer(wl, 1 % wl.n_layers, "cuda")
+    ws = torch.empty(B.structkv_pivot_workspace_bytes(sw.shape, max(wl.seq_lens)), dtype=torch.uint8, device="cuda")
+    ws.fill_(0x77)
+    rho = torch.full((wl.batch,), -1.0, device="cuda")
+    var = torch.full((wl.batch,), -1.0, device="cuda")
+    B.structkv_pivot_metrics(sw.shape, x.q_win, x.k, sw.cu, 0.1, rho, var, ws)
+    torch.cuda.synchronize()
+    _, _, _, probs = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads, wl.n_kv_heads,
+                                        wl.head_dim, wl.window, wl.seq_lens, causal=causal, want_probs=True)
+    rho_ref, var_ref = oracle.pivot_metrics(probs, 0.1)
+    tol = _tol(wl)
+    assert np.all(np.abs(rho.cpu().numpy() - rho_ref) <= tol * rho_ref)
+    n = np.array(wl.seq_lens, dtype=np.float64)
+    # the variance of a near-uniform head is a small difference of squares: floor at 1e-4 of (1/n)^2
+    assert np.all(np.abs(var.cpu().numpy() - var_ref) <= 2 * tol * var_ref + 1e-4 / n ** 2)
+    assert np.all((rho.cpu().numpy() >= 0.1 - 1e-6) & (rho.cpu().numpy() <= 1 + 1e-6))
+    # a different fraction, and the calls leave nothing behind that changes a repeat
+    B.structkv_pivot_metrics(sw.shape, x.q_win, x.k, sw.cu, 0.25, rho, var, ws)
+    torch.cuda.synchronize()
+    rho_ref25, _ = oracle.pivot_metrics(probs, 0.25)
+    assert np.all(np.abs(rho.cpu().numpy() - rho_ref25) <= tol * rho_ref25)
+
+
+def test_pivot_metrics_uniform_and_empty(B, sweep_mod):
+    # zero queries: every head is uniform, so sparsity = ceil(0.1 n)/n and variance = 0; an empty sequence gives 0
+    lens = [500, 0, 77]
+    sw = sweep_mod.LayerSweep(4, 2, 128, 32, torch.bfloat16, lens, [0, 0, 0])
+    q = torch.zeros(3, 4, 32, 128, dtype=torch.bfloat16, device="cuda")
+    k = torch.randn(2, sum(lens), 128, device="cuda").to(torch.bfloat16)
+    ws = torch.empty(B.structkv_pivot_workspace_bytes(sw.shape, max(lens)), dtype=torch.uint8, device="cuda")
+    rho = torch.full((3,), -1.0, device="cuda")
+    var = torch.full((3,), -1.0, device="cuda")
+    B.structkv_pivot_metrics(sw.shape, q, k, sw.cu, 0.1, rho, var, ws)
+    torch.cuda.synchronize()
+    r, v = rho.cpu().numpy(), var.cpu().numpy()
+    assert abs(r[0] - 50 / 500) < 1e-5 and abs(r[2] - 8 / 77) < 1e-5 and r[1] == 0.0
+    assert abs(v[0]) < 1e-12 and abs(v[2]) < 1e-10 and v[1] == 0.0
+
+
+def test_pivot_layer_of_a_sweep_matches_oracle(B, sweep_mod, oracle):
+    # Eq. 4-9 end to end on a small model: per-layer metrics from the GPU, transition score and L* from the library
+    wl = workloads.S_BF16_W64
+    L = 6
+    sw = make_sweep(sweep_mod, wl)
+    Hg, Rg, Vg, Ho, Ro, Vo = [], [], [], [], [], []
+    for l in range(L):
+        x = workloads.make_layer(wl, l % wl.n_layers, "cuda")
+        if l >= 3:                       # later layers: sharper queries, so the metrics move
+            x.q_win.mul_(1.0 + l)
+        sw.score(x.q_win, x.k)
+        rho, var = sw.pivot_metrics(x.q_win, x.k)
+        torch.cuda.synchronize()
+        Hg.append(float(sw.entropy[0])); Rg.append(float(rho[0])); Vg.append(float(var[0]))
+        _, ent, _, probs = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads,
+                                              wl.n_kv_heads, wl.head_dim, wl.window, wl.seq_lens, want_probs=True)
+        r, v = oracle.pivot_metrics(probs)
+        Ho.append(ent[0]); Ro.append(r[0]); Vo.append(v[0])
+    Tg, lg = B.structkv_transition_scores(Hg, Rg, Vg)
+    To, lo = oracle.transition_scores(Ho, Ro, Vo)
+    assert lg == lo and lg == 4                                   # the jump is between layers 2 and 3
+    assert np.allclose(Tg, To, rtol=0, atol=5e-3)
+
+
 # ------------------------------------------------------------------ whole sweeps
 
 def test_tiny_config_full_sweep(sweep_mod, oracle):
