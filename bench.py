@@ -171,8 +171,7 @@ def main():
     cpu = None
     if args.cpu_sample_layers > 0:
         import oracle
-        sys.path.insert(0, os.path.join(ROOT, "tests"))
-        from helpers import to_oracle_array
+        to_oracle_array = workloads.to_oracle_array
         ns = min(args.cpu_sample_layers, L)
         sample = sorted(set(int(round(i * (L - 1) / max(ns - 1, 1))) for i in range(ns)))
         C = np.zeros(wl.total_tokens)

@@ -5,13 +5,7 @@ import torch
 import workloads
 
 
-def to_oracle_array(t: torch.Tensor) -> np.ndarray:
-    """torch fp32 -> float32 ndarray; torch bf16 -> uint16 ndarray of the same bits."""
-    t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).numpy().view(np.uint16)
-    assert t.dtype == torch.float32
-    return t.numpy()
+to_oracle_array = workloads.to_oracle_array   # torch fp32 / bf16 tensor -> the host array the oracle takes
 
 
 def _tol(wl):

@@ -28,6 +28,7 @@ import math
 import zlib
 from typing import List, Sequence, Tuple
 
+import numpy as np
 import torch
 
 _MASK64 = (1 << 64) - 1
@@ -232,3 +233,13 @@ def make_layer(wl: Workload, layer: int, device="cpu") -> LayerInputs:
     k = k.to(dt)
     v = _randn((G, T, d), wl.stream_seed(layer, 3), device).to(dt)
     return LayerInputs(q, k, v)
+
+
+def to_oracle_array(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> the host array the CPU oracle takes, bit for bit: fp32 -> float32 ndarray,
+    bf16 -> uint16 ndarray of the same bit patterns (a conversion, no arithmetic)."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    assert t.dtype == torch.float32
+    return t.numpy()
