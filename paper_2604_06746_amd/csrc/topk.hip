@@ -22,7 +22,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kBins = 2048;               // digits 0 and 1: 11 bits
 constexpr int kLowBins = 1024;            // digit 2: 10 bits
-constexpr int kTargetPerBlock = 2048;     // scores per workgroup while the sequence is short enough
+constexpr int kTargetPerBlock = 2048;     // most scores a workgroup holds in registers (eight per thread)
+constexpr int kSmallTarget = 1024;        // share of a workgroup when the whole call is short: more, lighter
+constexpr int64_t kSmallTotal = 262144;   // workgroups shorten each kernel's serial part
 constexpr int kMaxBlocksPerSeq = 1024;    // beyond that a workgroup's share grows instead
 
 struct TopkWs {
@@ -333,9 +335,16 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
 }
 
 // upper bound of the workgroups one call launches
+inline int share_target(int64_t total_tokens) {
+  return total_tokens <= kSmallTotal ? kSmallTarget : kTargetPerBlock;
+}
+
 size_t max_blocks(int batch, int64_t total_tokens) {
   const size_t B = (size_t)(batch > 0 ? batch : 1);
-  size_t nb = (size_t)(total_tokens / kTargetPerBlock) + B;
+  // monotone in total_tokens, so a workspace sized for a long call also serves every shorter one
+  const int64_t small = total_tokens < kSmallTotal ? total_tokens : kSmallTotal;
+  const int64_t by_small = small / kSmallTarget, by_large = total_tokens / kTargetPerBlock;
+  size_t nb = (size_t)(by_small > by_large ? by_small : by_large) + B;
   if (nb > B * kMaxBlocksPerSeq) nb = B * kMaxBlocksPerSeq;
   return nb;
 }
@@ -355,16 +364,17 @@ hipError_t launch_topk(const float* scores, const SeqTable& seq_in, int keep_tai
   SeqTable seq = seq_in;
   const int B = seq.batch;
   if (B == 0) return hipSuccess;
-  // workgroups per sequence: about kTargetPerBlock scores each, at most kMaxBlocksPerSeq
+  // workgroups per sequence: about `target` scores each, at most kMaxBlocksPerSeq
+  const int target = share_target(seq.cu[B]);
   seq.chunk_start[0] = 0;
   for (int b = 0; b < B; ++b) {
     const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
-    int64_t nblk = seq.k[b] > 0 ? ceil_div(m, kTargetPerBlock) : 0;
+    int64_t nblk = seq.k[b] > 0 ? ceil_div(m, target) : 0;
     if (nblk > kMaxBlocksPerSeq) nblk = kMaxBlocksPerSeq;
     seq.chunk_start[b + 1] = seq.chunk_start[b] + (int)nblk;
   }
   const unsigned blocks = (unsigned)seq.chunk_start[B];
-  const size_t nb = max_blocks(B, seq.cu[B]);   // blocks <= nb: sum of ceil(m_b / 2048) <= total / 2048 + B
+  const size_t nb = max_blocks(B, seq.cu[B]);   // blocks <= nb: sum of ceil(m_b / target) <= total / target + B
   TopkWs ws;
   uint8_t* p = (uint8_t*)wsp;
   ws.hist = (uint32_t*)p;    p += align_up(sizeof(uint32_t) * 3 * (size_t)B * kBins, 256);
