@@ -77,6 +77,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
                ScorePlan* p) {
   const int gs = s.n_q_heads / s.n_kv_heads;
   p->R = gs * s.window;
+  p->kshare = 1;
   p->path = mfma_ok ? 0 : 1;
   if (p->path == 0) {
     // MFMA kernels: one wave owns RPC = 32*RB <= 64 rows and a chunk of KC keys.  A KV group with more rows is
@@ -141,13 +142,14 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
                           int64_t kst, const SeqTable& seq_in, float* indeg, float* entropy,
                           float* ent_head_out, float* probs, void* ws, size_t ws_bytes, hipStream_t st,
                           int step_mask = 15, float* centrality = nullptr, float lambda = 0.f,
-                          float inv_w = 0.f, float* groups = nullptr) {
+                          float inv_w = 0.f, float* groups = nullptr, int kshare = 1) {
   const structkv_shape& s = *shape;
   SeqTable seq = seq_in;
   const int B = seq.batch;
   const int64_t total = seq.cu[B];
   ScorePlan p;
   make_plan(s, &seq, B, total, mfma_eligible(s, q_win, k, ksh, kst), &p);
+  p.kshare = kshare;   // s.n_kv_heads % kshare == 0 (the caller's business)
   if (p.total_bytes > ws_bytes)
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, p.total_bytes);
   if ((int64_t)s.n_kv_heads * p.RC * p.n_chunks >= ((int64_t)1 << 31))
@@ -211,7 +213,8 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
                                         const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                         float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
                                         void* stream, int step_mask, float* centrality = nullptr,
-                                        float lambda = 0.f, float inv_w = 0.f, float* groups = nullptr) {
+                                        float lambda = 0.f, float inv_w = 0.f, float* groups = nullptr,
+                                        int kshare = 1) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -235,7 +238,7 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg_out, entropy_out,
                    entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask,
-                   centrality, lambda, inv_w, groups);
+                   centrality, lambda, inv_w, groups, kshare);
 }
 
 structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
@@ -481,10 +484,8 @@ struct PivotCarve {
 };
 // scratch for ONE sequence of at most n_max tokens at a time (sequences are processed one after the other)
 bool pivot_carve(const structkv_shape& s, int64_t n_max, structkv_shape* sub, PivotCarve* c) {
-  const int gs = s.n_q_heads / s.n_kv_heads;
   *sub = s;
-  sub->n_q_heads = gs;      // the gs query heads of one KV head, each as a group of its own
-  sub->n_kv_heads = gs;
+  sub->n_kv_heads = s.n_q_heads;   // every query head as a group of its own; gs consecutive ones share a K head
   const int hb = s.n_q_heads < kMaxBatch ? s.n_q_heads : kMaxBatch;   // heads per top-k call
   const size_t N = (size_t)(n_max > 0 ? n_max : 1);
   c->score_ws_bytes = structkv_workspace_bytes(sub, 1, n_max);
@@ -494,7 +495,7 @@ bool pivot_carve(const structkv_shape& s, int64_t n_max, structkv_shape* sub, Pi
   c->off_heads = off;     off += align_up(sizeof(float) * (size_t)s.n_q_heads * N, 256);
   c->off_indeg = off;     off += align_up(sizeof(float) * N, 256);
   c->off_idx = off;       off += align_up(sizeof(int32_t) * (size_t)s.n_q_heads * N, 256);
-  c->off_small = off;     off += align_up(sizeof(float) * (size_t)(3 * s.n_q_heads + 8), 256);
+  c->off_small = off;     off += align_up(sizeof(float) * (size_t)((2 * kPivotMaxSlices + 1) * s.n_q_heads + 8), 256);
   c->off_score_ws = off;  off += align_up(c->score_ws_bytes, 256);
   c->off_topk_ws = off;   off += align_up(c->topk_ws_bytes, 256);
   c->total = off;
@@ -547,25 +548,23 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
   float* heads = (float*)(w8 + c.off_heads);
   float* indeg = (float*)(w8 + c.off_indeg);
   int32_t* idx = (int32_t*)(w8 + c.off_idx);
-  float* rho_h = (float*)(w8 + c.off_small);
-  float* var_h = rho_h + shape->n_q_heads;
-  float* ent = var_h + shape->n_q_heads;           // entropy outputs of the sub-calls: not used here
+  float* part = (float*)(w8 + c.off_small);        // [Hq][slices][2] partial sums
+  float* ent = part + (size_t)2 * kPivotMaxSlices * shape->n_q_heads;   // entropy outputs of the scoring call: not used
   float* ent_h = ent + 4;
-  const int Hq = shape->n_q_heads, G = shape->n_kv_heads, gs = Hq / G, w = shape->window, d = shape->head_dim;
+  const int Hq = shape->n_q_heads, gs = Hq / shape->n_kv_heads, w = shape->window, d = shape->head_dim;
   const size_t e = shape->dtype == STRUCTKV_DTYPE_BF16 ? 2 : 4;
   hipStream_t hs = (hipStream_t)stream;
   for (int b = 0; b < batch; ++b) {
     const int64_t n = seq.cu[b + 1] - seq.cu[b];
     if (n > 0) {
-      // per-head in-degree D_h [Hq][n]: the gs heads of KV head g scored as gs groups that share one K head
+      // per-head in-degree D_h [Hq][n]: one scoring call in which every query head is a group of its own
+      // and the gs heads of a KV head read the same K head
       const int64_t cu1[2] = {0, n};
-      for (int g = 0; g < G; ++g) {
-        const uint8_t* qs = (const uint8_t*)q_win + ((size_t)b * Hq + (size_t)g * gs) * w * d * e;
-        const uint8_t* ks = (const uint8_t*)k + ((size_t)g * k_stride_head + (size_t)seq.cu[b] * k_stride_tok) * e;
-        st = score_layer_impl(&sub, qs, ks, 0, k_stride_tok, 1, cu1, indeg, ent, ent_h, w8 + c.off_score_ws,
-                              c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads + (size_t)g * gs * n);
-        if (st != STRUCTKV_OK) return st;
-      }
+      const uint8_t* qs = (const uint8_t*)q_win + (size_t)b * Hq * w * d * e;
+      const uint8_t* ks = (const uint8_t*)k + (size_t)seq.cu[b] * k_stride_tok * e;
+      st = score_layer_impl(&sub, qs, ks, k_stride_head, k_stride_tok, 1, cu1, indeg, ent, ent_h,
+                            w8 + c.off_score_ws, c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads, gs);
+      if (st != STRUCTKV_OK) return st;
       // the ceil(top_frac n) largest keys of every head: heads are the "sequences" of one selection call
       int64_t kk = (int64_t)std::ceil(top_frac * (double)n);
       if (kk < 1) kk = 1;
@@ -579,9 +578,10 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
                                   w8 + c.off_topk_ws, c.topk_ws_bytes, stream);
         if (st != STRUCTKV_OK) return st;
       }
-      SKV_HIP_CHECK(launch_pivot_heads(heads, Hq, n, idx, kk, 1.0f / (float)w, rho_h, var_h, hs));
+      SKV_HIP_CHECK(launch_pivot_heads(heads, Hq, n, idx, kk, 1.0f / (float)w, part, hs));
     }
-    SKV_HIP_CHECK(launch_pivot_finish(rho_h, var_h, Hq, n > 0 ? 1 : 0, sparsity_out + b, variance_out + b, hs));
+    SKV_HIP_CHECK(launch_pivot_finish(part, Hq, n, 1.0f / (float)w, n > 0 ? 1 : 0, sparsity_out + b,
+                                      variance_out + b, hs));
   }
   return STRUCTKV_OK;
 }

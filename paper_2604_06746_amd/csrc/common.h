@@ -44,6 +44,8 @@ struct ScorePlan {
   int RB;            // MFMA path: 32-row blocks per wave (1, 2 or 4)
   int NW;            // MFMA path: waves (row-chunks) per workgroup sharing the key tiles (1, 2 or 4)
   int CP;            // pass-2 column-sum planes per KV head (the waves of a workgroup add theirs up first)
+  int kshare;        // consecutive groups that read the same K head (1 in ordinary scoring; the per-head
+                     // scoring of the pivot metrics runs every query head as its own group: H_q/G)
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
   // workspace carve (byte offsets)
   size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;
@@ -70,9 +72,11 @@ hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, 
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);
 size_t topk_workspace_bytes(int batch, int64_t total_tokens);
+// pivot metrics: partial sums part [H][kPivotMaxSlices][2] of every head, then the means over the heads
+constexpr int kPivotMaxSlices = 64;
 hipError_t launch_pivot_heads(const float* heads, int H, int64_t n, const int32_t* idx, int64_t k, float inv_w,
-                              float* rho_h, float* var_h, hipStream_t st);
-hipError_t launch_pivot_finish(const float* rho_h, const float* var_h, int H, int valid, float* sparsity,
+                              float* part, hipStream_t st);
+hipError_t launch_pivot_finish(const float* part, int H, int64_t n, float inv_w, int valid, float* sparsity,
                                float* variance, hipStream_t st);
 hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);
 hipError_t launch_positions(const int64_t* pos_src, const SeqTable& seq, const int32_t* idx, int64_t* pos_dst,

@@ -60,7 +60,7 @@ template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896
 // NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring
 template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst,
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst, int kshare,
     SeqTable seq, int Hq, int G, int w, int causal, float c2, int R, int RC, int KC, int64_t n_chunks,
     float* __restrict__ stats, const float* __restrict__ lse2, float* __restrict__ colsum,
     int64_t total, float* __restrict__ probs) {
@@ -91,7 +91,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // workgroup -> (KV head g, group of row-chunks, key chunk); wave -> row-chunk inside the group
   const int wave = threadIdx.x >> 6;
   const int rcg = (RC + NW - 1) / NW;
-  const int g = blockIdx.x % G;
+  // groups that share a K head (kshare > 1) get workgroup numbers a multiple of G/kshare apart: with the
+  // usual eight KV heads they run on the same XCD at about the same time, and its L2 serves the re-reads
+  const int gp = blockIdx.x % G;
+  const int g = kshare == 1 ? gp : (gp % (G / kshare)) * kshare + gp / (G / kshare);
   const int64_t t = blockIdx.x / G;
   // a wave beyond the last row-chunk still helps loading tiles and keeps the barriers matched; it
   // computes on a valid chunk (the last one) and simply does not write results
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     }
   }
 
-  const uint16_t* kg = k + (int64_t)g * ksh + tok0 * kst;
+  const uint16_t* kg = k + (int64_t)(g / kshare) * ksh + tok0 * kst;
   // Tile layout in LDS: 16-byte piece (key, seg) sits at unit key*SEGS + (seg ^ swz(key)); any 16
   // consecutive keys at a fixed seg then hit 16 different groups of 4 banks (conflict-free operand reads).
   // Loader: instruction I, lane L writes unit I*64 + L, so it must fetch that unit's (key, seg).
@@ -395,7 +398,7 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
   const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.n_chunks;
   dim3 g((unsigned)grid), blk(64 * NW);
 #define SKV_ARGS                                                                                        \
-  g, blk, 0, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, seq, s.n_q_heads, s.n_kv_heads,      \
+  g, blk, 0, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
       s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs
   if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
   else if (probs == nullptr) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false>), SKV_ARGS);

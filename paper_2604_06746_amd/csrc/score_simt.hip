@@ -31,7 +31,7 @@ __device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float
 
 template <typename T>
 __global__ __launch_bounds__(256) void score_simt_kernel(
-    const T* __restrict__ q, const T* __restrict__ k, int64_t ksh, int64_t kst, SeqTable seq,
+    const T* __restrict__ q, const T* __restrict__ k, int64_t ksh, int64_t kst, int kshare, SeqTable seq,
     int Hq, int G, int d, int w, int causal, float c2, int R, int RC, int KC, int TKS,
     int64_t n_chunks, float* __restrict__ stats, const float* __restrict__ lse2,
     float* __restrict__ colsum, int64_t total, float* __restrict__ probs, int pass) {
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void score_simt_kernel(
   float M = kNegBig, Z = 0.f, E = 0.f;
   float nl = 0.f;
   if (pass == 2) nl = row_ok ? -lse2[(int64_t)b * G * R + (int64_t)g * R + row] : 0.f;
-  const T* kg = k + (int64_t)g * ksh + tok0 * kst;
+  const T* kg = k + (int64_t)(g / kshare) * ksh + tok0 * kst;   // kshare consecutive groups read one K head
 
   for (int64_t t0 = key0; t0 < key_end; t0 += TKS) {
     __syncthreads();
@@ -144,11 +144,11 @@ hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const 
   dim3 g((unsigned)grid), blk(256);
   if (s.dtype == STRUCTKV_DTYPE_F32) {
     hipLaunchKernelGGL(score_simt_kernel<float>, g, blk, smem, st, (const float*)q, (const float*)k, ksh,
-                       kst, seq, s.n_q_heads, s.n_kv_heads, d, s.window, s.causal, c2, p.R, p.RC, p.KC,
+                       kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, d, s.window, s.causal, c2, p.R, p.RC, p.KC,
                        TKS, p.n_chunks, stats, lse2, colsum, total, probs, pass);
   } else {
     hipLaunchKernelGGL(score_simt_kernel<__hip_bfloat16>, g, blk, smem, st, (const __hip_bfloat16*)q,
-                       (const __hip_bfloat16*)k, ksh, kst, seq, s.n_q_heads, s.n_kv_heads, d, s.window,
+                       (const __hip_bfloat16*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, d, s.window,
                        s.causal, c2, p.R, p.RC, p.KC, TKS, p.n_chunks, stats, lse2, colsum, total, probs,
                        pass);
   }
