@@ -43,7 +43,8 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-                         "(the sharding design is described in DESIGN.md).\n" % args.gpus)
+                         "(sequences and KV heads are independent, so several GPUs would each take a share "
+                         "of them and run this same sweep).\n" % args.gpus)
         sys.exit(2)
 
     import numpy as np

@@ -98,3 +98,31 @@ def sweep_against_oracle(sweep_mod, oracle, wl, layers, check_dormant=False):
     return sw, C
 
 
+
+
+def load_rational_sweep():
+    """tests/golden/rational_sweep.json as floats plus the fp32 inputs that realise it:
+    (doc, q [L][1,Hq,w,d] fp32, k [L][1,n,d] fp32).  Key j of a layer is (ln a_j, ln b_j, 0, 0)."""
+    import json, os
+    from fractions import Fraction
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "rational_sweep.json")) as f:
+        doc = json.load(f)
+    fr = lambda v: float(Fraction(v))
+    for layer in doc["layers"]:
+        layer["probs"] = np.array([[fr(x) for x in row] for row in layer["probs"]])
+        for key in ("indegree", "centrality_after"):
+            layer[key] = np.array([fr(x) for x in layer[key]])
+        for key in ("entropy", "sparsity", "variance"):
+            layer[key] = fr(layer[key]) if "/" in layer[key] else float(layer[key])
+    doc["lambda"] = fr(doc["lambda"])
+    doc["transition"]["T"] = [float(t) for t in doc["transition"]["T"]]
+    sh = doc["shape"]
+    qs, ks = [], []
+    for layer in doc["layers"]:
+        q = np.zeros((1, sh["n_q_heads"], sh["window"], sh["head_dim"]), np.float32)
+        q[0, 0, 0, 0], q[0, 0, 1, 0], q[0, 1, 0, 1], q[0, 1, 1, 1] = 1.0, 2.0, 1.0, 2.0
+        k = np.zeros((1, sh["n"], sh["head_dim"]), np.float32)
+        k[0, :, 0] = np.log(np.array(layer["head0_weights"], np.float64))
+        k[0, :, 1] = np.log(np.array(layer["head1_weights"], np.float64))
+        qs.append(q); ks.append(k)
+    return doc, qs, ks

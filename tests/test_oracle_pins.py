@@ -398,6 +398,50 @@ def test_transition_scores_hand_values(oracle):
     assert T.tolist() == pytest.approx([0.0, 0.0, 0.0, 1.0, 0.0])
 
 
+def test_golden_rational_sweep(oracle):
+    # tests/golden/rational_sweep.json: a four-layer sweep whose every value is an exact rational that follows from
+    # integer weights through Eq. 1-10 (written without the oracle).  The fp32 rounding of ln a_j moves a
+    # probability by about 1e-7 relative, hence the 2e-6 below.
+    # catches: a wrong softmax axis or GQA mapping, a missing 1/w or lambda, pooling over the wrong axis,
+    # a wrong difference sign or normalisation in the transition score, a tie broken the wrong way
+    from helpers import load_rational_sweep
+    doc, qs, ks = load_rational_sweep()
+    sh = doc["shape"]
+    n, w = sh["n"], sh["window"]
+    C = np.zeros(n)
+    H, R, V = [], [], []
+    for layer, q, k in zip(doc["layers"], qs, ks):
+        assert layer["probs"].sum(1) == pytest.approx(1.0, abs=1e-15)        # the fixture itself is consistent
+        D, ent, _, probs = oracle.score_layer(q, k, sh["n_q_heads"], sh["n_kv_heads"], sh["head_dim"], w, [n],
+                                              scale=sh["scale"], want_probs=True)
+        assert probs[0].reshape(-1, n) == pytest.approx(layer["probs"], rel=2e-6)
+        assert D == pytest.approx(layer["indegree"], rel=2e-6)
+        assert ent[0] == pytest.approx(layer["entropy"], rel=2e-6)
+        oracle.accumulate(C, D, doc["lambda"], 1.0 / w)
+        assert C == pytest.approx(layer["centrality_after"], rel=2e-6)
+        rho, var = oracle.pivot_metrics(probs, doc["top_frac"])
+        assert rho[0] == pytest.approx(layer["sparsity"], rel=2e-6)
+        assert var[0] == pytest.approx(layer["variance"], rel=1e-5)
+        H.append(layer["entropy"]); R.append(layer["sparsity"]); V.append(layer["variance"])
+    assert oracle.select_topk(C, [n], [2], 0)[0].tolist() == doc["selection"]["top2"]
+    assert oracle.select_topk(C, [n], [1], w)[0].tolist() == doc["selection"]["top1_of_earlier_plus_window"]
+    T, ls = oracle.transition_scores(H, R, V, doc["transition_weights"])
+    assert T.tolist() == pytest.approx(doc["transition"]["T"], abs=1e-12)
+    assert ls == doc["transition"]["pivot_layer"]
+
+
+def test_golden_fixture_is_reproducible(tmp_path):
+    # the committed generator rewrites exactly the committed fixture (no oracle, no GPU involved)
+    import importlib.util, os, shutil
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    shutil.copy(os.path.join(here, "make_rational_sweep.py"), tmp_path / "make_rational_sweep.py")
+    spec = importlib.util.spec_from_file_location("make_rational_sweep", tmp_path / "make_rational_sweep.py")
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.main()
+    assert (tmp_path / "rational_sweep.json").read_text() == open(os.path.join(here, "rational_sweep.json")).read()
+
+
 def test_planted_hubs_selected_by_centrality(oracle):
     # hubs that are dormant in half of the layers are missed by single-layer scores but kept by C
     wl = workloads.S_BF16
