@@ -203,6 +203,21 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
                                        void* stream);
 
 /*
+ * structkv_score_layer and structkv_pivot_metrics from ONE scoring of the layer, for the layers on which the
+ * pivot detector is still running (paper Eq. 2, 4, 5, 6): the per-head scoring that the metrics need also yields
+ * the in-degree and the entropies.  Outputs as in structkv_score_layer (indeg_out DEVICE fp32 [total],
+ * entropy_out DEVICE fp32 [B], entropy_per_head_out DEVICE fp32 [B][H_q] or NULL) and structkv_pivot_metrics.
+ * indeg_out sums the heads in another order than structkv_score_layer does: equal to it within fp32 rounding, not
+ * bit for bit.  Workspace and errors as structkv_pivot_metrics.
+ */
+structkv_status structkv_score_layer_pivot(const structkv_shape* shape, const void* q_win, const void* k,
+                                           int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                           const int64_t* cu_seqlens, double top_frac, float* indeg_out,
+                                           float* entropy_out, float* entropy_per_head_out, float* sparsity_out,
+                                           float* variance_out, void* workspace, size_t workspace_bytes,
+                                           void* stream);
+
+/*
  * Transition score and pivot layer (paper Eq. 7-9), HOST arithmetic on HOST arrays of per-layer metrics
  * (layers 0 .. n_layers-1 of the un-pruned prefix):  dM_l = M_l - M_{l-1} for l >= 1; each metric's differences
  * are min-max scaled to [0,1] over l = 1 .. n_layers-1 (a metric whose differences are all equal contributes 0);

@@ -28,7 +28,7 @@ EXPORTS = (
     "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_score_layer_groups",
     "structkv_select_topk",
     "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
-    "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_transition_scores",
+    "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_score_layer_pivot", "structkv_transition_scores",
     "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
 )
 
@@ -79,6 +79,9 @@ _lib.structkv_block_scores.restype = _i32
 _lib.structkv_block_scores.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
 _lib.structkv_pivot_workspace_bytes.restype = _sz
 _lib.structkv_pivot_workspace_bytes.argtypes = [_sp, _i64]
+_lib.structkv_score_layer_pivot.restype = _i32
+_lib.structkv_score_layer_pivot.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, ctypes.c_double, _vp, _vp, _vp, _vp,
+                                            _vp, _vp, _sz, _vp]
 _lib.structkv_pivot_metrics.restype = _i32
 _lib.structkv_pivot_metrics.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, ctypes.c_double, _vp, _vp, _vp, _sz,
                                         _vp]
@@ -252,6 +255,20 @@ def structkv_pivot_metrics(shape: structkv_shape, q_win: torch.Tensor, k: torch.
                                        len(cu_seqlens) - 1, cu, top_frac, _ptr(sparsity_out), _ptr(variance_out),
                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
                                        _stream(stream)))
+
+
+def structkv_score_layer_pivot(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
+                               cu_seqlens: Sequence[int], top_frac: float, indeg_out: torch.Tensor,
+                               entropy_out: torch.Tensor, entropy_per_head_out: Optional[torch.Tensor],
+                               sparsity_out: torch.Tensor, variance_out: torch.Tensor, workspace: torch.Tensor,
+                               stream=None) -> None:
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous()
+    cu = _host_i64(cu_seqlens)
+    _check(_lib.structkv_score_layer_pivot(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
+                                           len(cu_seqlens) - 1, cu, top_frac, _ptr(indeg_out), _ptr(entropy_out),
+                                           _ptr(entropy_per_head_out), _ptr(sparsity_out), _ptr(variance_out),
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                           _stream(stream)))
 
 
 def structkv_transition_scores(entropy: Sequence[float], sparsity: Sequence[float], variance: Sequence[float],

@@ -511,10 +511,12 @@ size_t structkv_pivot_workspace_bytes(const structkv_shape* shape, int64_t max_s
   return c.total;
 }
 
-structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* q_win, const void* k,
-                                       int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
-                                       const int64_t* cu_seqlens, double top_frac, float* sparsity_out,
-                                       float* variance_out, void* workspace, size_t workspace_bytes, void* stream) {
+// indeg_out / entropy_out / entropy_head_out: optional, the per-head scoring call's own totals
+static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win, const void* k,
+                                  int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                  const int64_t* cu_seqlens, double top_frac, float* indeg_out, float* entropy_out,
+                                  float* entropy_head_out, float* sparsity_out, float* variance_out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -562,8 +564,10 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
       const int64_t cu1[2] = {0, n};
       const uint8_t* qs = (const uint8_t*)q_win + (size_t)b * Hq * w * d * e;
       const uint8_t* ks = (const uint8_t*)k + (size_t)seq.cu[b] * k_stride_tok * e;
-      st = score_layer_impl(&sub, qs, ks, k_stride_head, k_stride_tok, 1, cu1, indeg, ent, ent_h,
-                            w8 + c.off_score_ws, c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads, gs);
+      st = score_layer_impl(&sub, qs, ks, k_stride_head, k_stride_tok, 1, cu1,
+                            indeg_out ? indeg_out + seq.cu[b] : indeg, entropy_out ? entropy_out + b : ent,
+                            entropy_head_out ? entropy_head_out + (size_t)b * Hq : ent_h, w8 + c.off_score_ws,
+                            c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads, gs);
       if (st != STRUCTKV_OK) return st;
       // the ceil(top_frac n) largest keys of every head: heads are the "sequences" of one selection call
       int64_t kk = (int64_t)std::ceil(top_frac * (double)n);
@@ -582,8 +586,36 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
     }
     SKV_HIP_CHECK(launch_pivot_finish(part, Hq, n, 1.0f / (float)w, n > 0 ? 1 : 0, sparsity_out + b,
                                       variance_out + b, hs));
+    if (n == 0) {   // an empty sequence scores nothing: its entropies are zero, as in structkv_score_layer
+      if (entropy_out) SKV_HIP_CHECK(launch_zero_floats(entropy_out + b, 1, hs));
+      if (entropy_head_out) SKV_HIP_CHECK(launch_zero_floats(entropy_head_out + (size_t)b * Hq, Hq, hs));
+    }
   }
   return STRUCTKV_OK;
+}
+
+structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* q_win, const void* k,
+                                       int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                       const int64_t* cu_seqlens, double top_frac, float* sparsity_out,
+                                       float* variance_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return pivot_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, top_frac, nullptr, nullptr,
+                    nullptr, sparsity_out, variance_out, workspace, workspace_bytes, stream);
+}
+
+structkv_status structkv_score_layer_pivot(const structkv_shape* shape, const void* q_win, const void* k,
+                                           int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
+                                           const int64_t* cu_seqlens, double top_frac, float* indeg_out,
+                                           float* entropy_out, float* entropy_per_head_out, float* sparsity_out,
+                                           float* variance_out, void* workspace, size_t workspace_bytes,
+                                           void* stream) {
+  if (batch > 0 && !entropy_out) { clear_error(); return fail(STRUCTKV_ERR_INVALID_ARG, "entropy_out is NULL"); }
+  if (batch > 0 && cu_seqlens && cu_seqlens[batch] > 0 && !indeg_out) {
+    clear_error();
+    return fail(STRUCTKV_ERR_INVALID_ARG, "indeg_out is NULL");
+  }
+  return pivot_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, top_frac, indeg_out,
+                    entropy_out, entropy_per_head_out, sparsity_out, variance_out, workspace, workspace_bytes,
+                    stream);
 }
 
 structkv_status structkv_transition_scores(const double* entropy, const double* sparsity, const double* variance,

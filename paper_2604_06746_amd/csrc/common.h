@@ -76,6 +76,7 @@ size_t topk_workspace_bytes(int batch, int64_t total_tokens);
 constexpr int kPivotMaxSlices = 64;
 hipError_t launch_pivot_heads(const float* heads, int H, int64_t n, const int32_t* idx, int64_t k, float inv_w,
                               float* part, hipStream_t st);
+hipError_t launch_zero_floats(float* p, int n, hipStream_t st);   // a fill kernel (safe inside a captured graph)
 hipError_t launch_pivot_finish(const float* part, int H, int64_t n, float inv_w, int valid, float* sparsity,
                                float* variance, hipStream_t st);
 hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);

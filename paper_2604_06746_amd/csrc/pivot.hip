@@ -80,7 +80,18 @@ __global__ __launch_bounds__(256) void pivot_finish_kernel(const float* __restri
   }
 }
 
+__global__ void zero_floats_kernel(float* __restrict__ p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
 }  // namespace
+
+hipError_t launch_zero_floats(float* p, int n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(zero_floats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
 
 int pivot_slices(int64_t n) {
   const int64_t p = (n + 8191) / 8192;

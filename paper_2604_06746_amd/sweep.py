@@ -73,6 +73,15 @@ class LayerSweep:
                                  self._pivot_ws, stream)
         return self.sparsity, self.variance
 
+    def score_pivot(self, q_win: torch.Tensor, k: torch.Tensor, top_frac: float = 0.1, stream=None):
+        """score() and pivot_metrics() from one scoring of the layer: fills indeg, entropy, entropy_per_head and
+        returns (sparsity [B], variance [B])."""
+        if getattr(self, "_pivot_ws", None) is None:
+            self.pivot_metrics(q_win, k, top_frac, stream)          # allocates the scratch and the outputs
+        B.structkv_score_layer_pivot(self.shape, q_win, k, self.cu, top_frac, self.indeg, self.entropy,
+                                     self.entropy_per_head, self.sparsity, self.variance, self._pivot_ws, stream)
+        return self.sparsity, self.variance
+
     def select_kv(self, stream=None) -> None:
         """Eq. 13: per-layer storage indices from this layer's scores."""
         B.structkv_select_topk(self.indeg, self.cu, self.k_per_seq, self.keep_tail, self.idx_kv,

@@ -196,3 +196,12 @@ def test_pivot_metrics_arguments(B):
     assert call(ws=None) == B.STRUCTKV_ERR_WORKSPACE
     assert call(wsb=need - 256) == B.STRUCTKV_ERR_WORKSPACE and "need" in B.structkv_last_error()
     assert call(batch=0) == B.STRUCTKV_OK
+
+    def fused(indeg=fake, ent=fake, frac=0.1, ws=fake, batch=1):
+        return lib.structkv_score_layer_pivot(ctypes.byref(shape), fake, fake, 100 * 128, 128, batch, cu, float(frac),
+                                              indeg, ent, None, fake, fake, ws, need, None)
+    assert fused(indeg=None) == B.STRUCTKV_ERR_INVALID_ARG and "indeg_out" in B.structkv_last_error()
+    assert fused(ent=None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(frac=-1.0) == B.STRUCTKV_ERR_INVALID_ARG
+    assert fused(ws=None) == B.STRUCTKV_ERR_WORKSPACE
+    assert fused(batch=0) == B.STRUCTKV_OK

@@ -439,6 +439,30 @@ def test_pivot_metrics_match_oracle(B, sweep_mod, oracle, name, causal):
     assert np.all(np.abs(rho.cpu().numpy() - rho_ref25) <= tol * rho_ref25)
 
 
+@pytest.mark.parametrize("name,causal", [("s_bf16_w64", False), ("s_bf16_ragged", True), ("s_f32_ragged", False)])
+def test_score_layer_pivot_equals_the_two_calls(sweep_mod, oracle, name, causal):
+    # one per-head scoring yields the layer's scores AND the pivot metrics
+    wl = workloads.WORKLOADS[name]
+    sw = make_sweep(sweep_mod, wl, causal)
+    x = workloads.make_layer(wl, 0, "cuda")
+    sw.score(x.q_win, x.k)
+    rho, var = sw.pivot_metrics(x.q_win, x.k)
+    torch.cuda.synchronize()
+    D, ent, ent_h = sw.indeg.clone(), sw.entropy.clone(), sw.entropy_per_head.clone()
+    rho, var = rho.clone(), var.clone()
+    sw.indeg.fill_(-1.0); sw.entropy.fill_(-1.0); sw.entropy_per_head.fill_(-1.0)
+    sw.sparsity.fill_(-1.0); sw.variance.fill_(-1.0)
+    r2, v2 = sw.score_pivot(x.q_win, x.k)
+    torch.cuda.synchronize()
+    assert torch.equal(r2, rho) and torch.equal(v2, var)                     # the same kernels on the same data
+    assert_close_floor(sw.indeg.cpu().numpy(), D.cpu().numpy(), 1e-5, "in-degree from the per-head scoring")
+    assert torch.allclose(sw.entropy, ent, rtol=1e-5, atol=1e-6)
+    assert torch.allclose(sw.entropy_per_head, ent_h, rtol=1e-5, atol=1e-6)
+    Dref, eref, _, _ = oracle_layer(oracle, wl, x, causal)
+    assert_close_floor(sw.indeg.cpu().numpy(), Dref, _tol(wl), "in-degree vs oracle")
+    assert_entropy(sw.entropy.cpu().numpy()[:wl.batch], eref, _tol(wl))
+
+
 def test_pivot_metrics_uniform_and_empty(B, sweep_mod):
     # zero queries: every head is uniform, so sparsity = ceil(0.1 n)/n and variance = 0; an empty sequence gives 0
     lens = [500, 0, 77]
