@@ -53,12 +53,6 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// s_waitcnt lgkmcnt(N) tied to a value: whatever reads `x` afterwards is ordered behind the wait
-template <int N, class T>
-__device__ __forceinline__ void wait_lgkm_for(T& x) {
-  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
-}
-
 // most keys a workgroup may be given (pass 2 keeps one fp32 column sum per key in LDS)
 // (one-wave workgroups: 896, so that eight of them -- 16 KB ring + 3.5 KB each -- still share a CU's 160 KB)
 template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896);
@@ -82,13 +76,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // pass 2: the workgroup's column sums of its whole key chunk collect in LDS and are written out once at the
   // end, so that the key loop holds no global store (a store between the tile loads would make the
   // s_waitcnt vmcnt(N) below wait for younger loads than it has to).  With several waves, each wave parks
-  // its sums of tile s (both lane halves, 64 floats: no cross-lane exchange in the loop) in csbuf[s % 3] and
+  // its sums of tile s (both lane halves, 64 floats: no cross-lane exchange in the loop) in csbuf[s % 4] and
   // one wave adds them up, halves first, then in wave order, two tiles later: by then
   // every wave has waited for the LDS reads of tile s+1 (LDS operations complete in order, so its older
   // csbuf write is done) and has passed the barrier of tile s+2 -- no extra wait, no extra barrier.
+  // Both buffers live in DYNAMIC LDS behind the ring (csout [KCAP] floats, then csbuf [4][NW][64] floats;
+  // kColsumLdsBytes below) and are addressed by number, through asm: the ring stays the kernel's only LDS object,
+  // whose reads the compiler then never orders behind the tile loads in flight (with the buffers as static
+  // arrays, or with their addresses taken, it loses track and waits for ALL tile loads before LDS accesses).
   constexpr int KCAP = PASS == 2 ? kKeyCap<NW> : 1;
-  __shared__ float csout[KCAP];
-  __shared__ float csbuf[PASS == 2 && NW > 1 ? 3 : 1][PASS == 2 && NW > 1 ? NW : 1][PASS == 2 && NW > 1 ? 64 : 1];
   // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
   constexpr int VPM = PASS == 1 ? 8 : 4;
 
@@ -200,35 +196,17 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       }
     }
   };
-  // Operands of the tile being consumed.  The eight LDS reads are written as asm so that the MFMAs of row block
-  // 0 can wait for them ONE BY ONE (LDS operations complete in order: lgkmcnt <= 7 means the oldest of eight
-  // is there); left to itself the compiler waits for all eight before the first MFMA.  Any other LDS operation
-  // the compiler places around them only makes these waits stricter, never too weak; the loop holds no scalar
-  // load (those share the counter and complete out of order).
+  // Operands of the tile being consumed.  Plain loads: an asm ds_read whose result is waited for by a later
+  // asm statement is NOT safe -- the compiler may copy the "loaded" register in between, before the data has
+  // arrived (it did, in the software-pipelined loop below).
   bf16x8 kf[KS];
-  uint32_t koff[KS];   // per-lane byte offset of each k-step's 16 bytes inside a tile
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = (uint32_t)((l32 * SEGS + ((2 * ks + lh) ^ swz(l32))) * 16);
-  const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_ptr_t)ring;
   auto read_tile = [&](int s_idx) __attribute__((always_inline)) {
-    const uint32_t slot = ring_lds + (uint32_t)((s_idx % NBUF) * TILE_BYTES);
+    const uint8_t* slot = ring + (s_idx % NBUF) * TILE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("ds_read_b128 %0, %1" : "=v"(kf[ks]) : "v"(slot + koff[ks]));
-  };
-  // row block 0's MFMAs, each behind the wait for its own operand
-  auto first_mfma_block = [&](floatx16& acc) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    auto one = [&](auto ks_tag) __attribute__((always_inline)) {
-      constexpr int ks = decltype(ks_tag)::value;
-      wait_lgkm_for<KS - 1 - ks>(kf[ks]);
-      if (PASS == 1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[0][ks], acc, 0, 0, 0);
-      else           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][ks], kf[ks], acc, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);   // keeps this MFMA ahead of the next operand's wait
-    };
-    one(IntC<0>{}); one(IntC<1>{}); one(IntC<2>{}); one(IntC<3>{});
-    if constexpr (KS == 8) { one(IntC<4>{}); one(IntC<5>{}); one(IntC<6>{}); one(IntC<7>{}); }
-    if constexpr (PASS == 2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug[0], kaug, acc, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks) {
+      const int seg = 2 * ks + lh;
+      kf[ks] = *reinterpret_cast<const bf16x8*>(slot + (l32 * SEGS + (seg ^ swz(l32))) * 16);
+    }
   };
 
   float M[NRB], Z[NRB], E[NRB];   // pass 1: statistics of this lane's query row in each row block
@@ -325,48 +303,33 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // compiler cannot always rule out that the tile loads in flight (which write LDS too) alias them, and then
   // waits for ALL of those loads (vmcnt 0) in front of the access, which empties the ring every tile.
   // The column-sum buffers never overlap the ring, so no such wait is needed.
-  const uint32_t csbuf_lds = (uint32_t)(uintptr_t)(lds_ptr_t)&csbuf[0][0][0];
-  const uint32_t csout_lds = (uint32_t)(uintptr_t)(lds_ptr_t)&csout[0];
+  const uint32_t lane_x4_lo = (uint32_t)l32 * 4u, thread_x4 = (uint32_t)threadIdx.x * 4u;
+  const uint32_t csout_lds = __builtin_amdgcn_groupstaticsize();   // dynamic LDS starts where the static part ends
+  const uint32_t csbuf_lds = csout_lds + (uint32_t)KCAP * 4u;
   auto flush_colsum = [&](int s_idx) __attribute__((always_inline)) {
     if (PASS == 2 && NW > 1 && wave == (s_idx % NW) && lh == 0) {
-      const uint32_t a = csbuf_lds + (uint32_t)(((s_idx % 3) * NW) * 256 + l32 * 4);
+      // (scalar part of each address through readfirstlane: it stays in a scalar register and is added to the
+      // lane part at the point of use, instead of becoming one more loop-carried vector register)
+      const uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(((s_idx % 4) * NW) * 256))) + lane_x4_lo;
+      // reads AND their wait in one asm statement each (nothing can get between a read and its wait)
       float lo[NW], hi[NW];
-#pragma unroll
-      for (int wv = 0; wv < NW; ++wv) {
-        asm volatile("ds_read_b32 %0, %1" : "=v"(lo[wv]) : "v"(a + wv * 256));
-        asm volatile("ds_read_b32 %0, %1" : "=v"(hi[wv]) : "v"(a + wv * 256 + 128));
-      }
-#pragma unroll
-      for (int wv = 0; wv < NW; ++wv) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[wv]), "+v"(hi[wv]));
+#define SKV_RD(WV)                                                                                             \
+      asm volatile("ds_read_b32 %0, %2 offset:%3\n\tds_read_b32 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"      \
+                   : "=&v"(lo[WV]), "=&v"(hi[WV]) : "v"(a), "n"((WV) * 256), "n"((WV) * 256 + 128))
+      SKV_RD(0);
+      if constexpr (NW > 1) { SKV_RD(1); }
+      if constexpr (NW > 2) { SKV_RD(2); SKV_RD(3); }
+#undef SKV_RD
       // a wave's sum of a key = its lower lane half's + its upper lane half's; then the waves in order
       float cs = lo[0] + hi[0];
 #pragma unroll
       for (int wv = 1; wv < NW; ++wv) cs += lo[wv] + hi[wv];
-      asm volatile("ds_write_b32 %0, %1" : : "v"(csout_lds + (uint32_t)((32 * s_idx + l32) * 4)), "v"(cs) : "memory");
+      const uint32_t o = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csout_lds + (uint32_t)(128 * s_idx))) + lane_x4_lo;
+      asm volatile("ds_write_b32 %0, %1" : : "v"(o), "v"(cs) : "memory");
     }
   };
   floatx16 acc0, acc1;
 
-  // One tile of 32 keys whose operands are in kf: row block rb+1's MFMAs run under row block rb's softmax.
-  // (row block 0's MFMAs are issued by the caller, straight after the operand reads)
-  auto sub_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
-    using MT = decltype(masked_tag);
-    auto step = [&](auto rb_tag) __attribute__((always_inline)) {
-      constexpr int rb = decltype(rb_tag)::value;
-      floatx16& mine = (rb & 1) ? acc1 : acc0;
-      floatx16& other = (rb & 1) ? acc0 : acc1;
-      if (rb + 1 < NRB) {
-        mfma_block(other, kf, IntC<(rb + 1 < NRB ? rb + 1 : 0)>{});
-        softmax_block(MT{}, mine, rb_tag, jbase);
-        interleave_hint();
-      } else {
-        softmax_block(MT{}, mine, rb_tag, jbase);
-      }
-    };
-    step(IntC<0>{});
-    if constexpr (NRB > 1) step(IntC<1>{});
-    if constexpr (NRB > 2) { step(IntC<2>{}); step(IntC<3>{}); }
-  };
   // pass 2: park this tile's column sums.  ONE store in the loop body, outside the masked / unmasked variants
   // of sub_tile: two copies get merged by the compiler into a store that has lost its alias information, and it
   // then waits for every outstanding tile load (which also write LDS) before it.
@@ -379,55 +342,77 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
           asm volatile("ds_write_b32 %0, %1" : : "v"(csout_lds + (uint32_t)((jbase - key0 + l32) * 4)), "v"(cs) : "memory");
       } else {
         // both lane halves park their sums: no cross-lane exchange in the key loop
-        const uint32_t a = csbuf_lds + (uint32_t)((((((jbase - key0) >> 5) % 3) * NW + wave) * 64 + lane) * 4);
+        const uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane(
+                               (int)(csbuf_lds + (uint32_t)(((((jbase - key0) >> 5) % 4) * NW) * 256))) + thread_x4;
         asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(live ? cs : 0.f) : "memory");
       }
       cs0 = 0.f; cs1 = 0.f;
     }
   };
-  // prologue: request the first PD tiles
-#pragma unroll
-  for (int i = 0; i < PD; ++i)
-    if (i < nsub) issue_tile(i);
-  for (int s = 0; s < nsub; ++s) {
-    // my share of tile s has landed when at most the later requests (up to PD-1 tiles) are outstanding
+  // my share of tile s has landed when at most the later requests (up to PD-1 tiles) are outstanding; then the
+  // barrier: a plain s_barrier, not __syncthreads(), whose fence waits for ALL outstanding loads and would drain
+  // the ring.  After it everybody's share of tile s is in LDS (each wave waited for its own loads) and everybody
+  // is done reading tile s-1's slot, which the next request overwrites.
+  auto tile_ready = [&](int s) __attribute__((always_inline)) {
     const int later = min(PD - 1, nsub - 1 - s);
     if (later >= 3) wait_vmcnt<3 * IPW>();
     else if (later == 2) wait_vmcnt<2 * IPW>();
     else if (later == 1) wait_vmcnt<IPW>();
     else wait_vmcnt<0>();
-    // Plain s_barrier, not __syncthreads(): the fence in the latter waits for ALL outstanding loads, which
-    // would drain the ring.  After the barrier everybody's share of tile s is in LDS (each wave waited for
-    // its own loads above) and everybody is done reading tile s-1's slot.
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (s + PD < nsub) issue_tile(s + PD);   // goes into the slot tile s-1 just left
-    // Operand reads and row block 0's MFMAs stay in one basic block, ahead of every branch: the compiler then
-    // waits for the reads one by one (lgkmcnt 7, 6, ...) instead of for all eight before the first MFMA.
-    read_tile(s);
-    first_mfma_block(acc0);
-    // the column sums of tile s-2 are added up under those MFMAs, when the wave has nothing else to issue
-    if (s >= 2) flush_colsum(s - 2);
-    const int jbase = key0 + 32 * s;
-    // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
-    const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
-    if (!masked) sub_tile(BoolC<false>{}, jbase);
-    else         sub_tile(BoolC<true>{}, jbase);
-    park_colsum(jbase);
+    if (s + PD < nsub) issue_tile(s + PD);
+  };
+  // prologue: request the first PD tiles
+#pragma unroll
+  for (int i = 0; i < PD; ++i)
+    if (i < nsub) issue_tile(i);
+  {
+    // one tile per iteration: row block 1's MFMAs run under row block 0's softmax
+    auto rest_of_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
+      if constexpr (NRB == 2) {
+        mfma_block(acc1, kf, IntC<NRB - 1>{});
+        softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
+        interleave_hint();
+        softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase);
+      } else {
+        softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
+      }
+    };
+    for (int s = 0; s < nsub; ++s) {
+      tile_ready(s);
+      read_tile(s);
+      mfma_block(acc0, kf, IntC<0>{});
+      // the column sums of tile s-2 are added up under those MFMAs, when the wave has nothing else to issue
+      // (parked in iteration s-2; every wave has since waited for the operand reads of tile s-1 and passed the
+      // barrier of tile s)
+      if (s >= 2) flush_colsum(s - 2);
+      const int jbase = key0 + 32 * s;
+      const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
+      if (!masked) rest_of_tile(BoolC<false>{}, jbase);
+      else         rest_of_tile(BoolC<true>{}, jbase);
+      park_colsum(jbase);
+    }
   }
 
   if (PASS == 2) {
     if (NW > 1) {
+      // the asm LDS writes are unknown to the compiler, so the barriers' own fences do not wait for them
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       __syncthreads();
-      if (nsub >= 2) flush_colsum(nsub - 2);
-      if (nsub >= 1) flush_colsum(nsub - 1);
+#pragma unroll
+      for (int t = 3; t >= 1; --t)
+        if (nsub >= t) flush_colsum(nsub - t);   // (the oldest of the three may have been added up already)
     }
-    // the asm LDS writes above are unknown to the compiler, so the barrier's own fence does not wait for them
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __syncthreads();
     float* out = colsum + (int64_t)plane * total + tok0 + key0;
-    for (int i = threadIdx.x; i < key_end - key0; i += 64 * NW) out[i] = csout[i];
+    for (int i = threadIdx.x; i < key_end - key0; i += 64 * NW) {
+      float v;
+      asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(csout_lds + (uint32_t)i * 4u));
+      out[i] = v;
+    }
   }
 
   if (PASS == 1) {
@@ -457,8 +442,11 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
                            hipStream_t st) {
   const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.n_chunks;
   dim3 g((unsigned)grid), blk(64 * NW);
+  // pass 2: dynamic LDS for the column sums of the key chunk and the waves' parked sums
+  const unsigned cs_bytes = (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
+  const unsigned dyn = pass == 1 ? 0u : cs_bytes;
 #define SKV_ARGS                                                                                        \
-  g, blk, 0, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
+  g, blk, dyn, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
       s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs
   if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
   else if (probs == nullptr) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false>), SKV_ARGS);
