@@ -81,7 +81,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // every wave has waited for the LDS reads of tile s+1 (LDS operations complete in order, so its older
   // csbuf write is done) and has passed the barrier of tile s+2 -- no extra wait, no extra barrier.
   // Both buffers live in DYNAMIC LDS behind the ring (csout [KCAP] floats, then csbuf [4][NW][64] floats;
-  // kColsumLdsBytes below) and are addressed by number, through asm: the ring stays the kernel's only LDS object,
+  // the launcher passes their size) and are addressed by number, through asm: the ring stays the kernel's only LDS object,
   // whose reads the compiler then never orders behind the tile loads in flight (with the buffers as static
   // arrays, or with their addresses taken, it loses track and waits for ALL tile loads before LDS accesses).
   constexpr int KCAP = PASS == 2 ? kKeyCap<NW> : 1;
