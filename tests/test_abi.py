@@ -205,3 +205,21 @@ def test_pivot_metrics_arguments(B):
     assert fused(frac=-1.0) == B.STRUCTKV_ERR_INVALID_ARG
     assert fused(ws=None) == B.STRUCTKV_ERR_WORKSPACE
     assert fused(batch=0) == B.STRUCTKV_OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU per box: bench.py --gpus N with N > 1 exits with a message before it touches torch or the GPU
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_entry_points_exist():
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("graft_entry", os.path.join(root, "__graft_entry__.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert callable(mod.build) and callable(mod.smoke)
