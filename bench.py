@@ -144,6 +144,21 @@ def main():
         n_meas = len(all_evs)
     kern_us = {k: (1e3 * v / n_meas if n_meas else None) for k, v in acc_ms.items()}
 
+    # ---- a plain device-to-device copy, as the practical HBM ceiling beside the data-sheet peak ----
+    copy_gbs = None
+    if n_meas:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ce[0].record(stream)
+        for _ in range(5):
+            dst.copy_(src)
+        ce[1].record(stream)
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2.0 * src.numel() / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9     # bytes read + written
+        del src, dst
+
     k_bytes = wl.n_kv_heads * wl.head_dim * wl.elem_bytes * wl.total_tokens       # K read once, per launch
     rows = sum(k + wl.window for k in wl.k_per_seq)
     gather_bytes = 2 * 2 * rows * wl.n_kv_heads * wl.head_dim * wl.elem_bytes + 4 * rows
@@ -161,7 +176,8 @@ def main():
                 traffic = None
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": round(kern_us[dom], 2)}
+                    "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": round(kern_us[dom], 2),
+                    "measured_copy_GBs": round(copy_gbs, 1), "frac_of_measured_copy": round(achieved / copy_gbs, 4)}
         score_us = sum(kern_us[k] for k in names[:4])
         qk_flops = 2.0 * wl.n_q_heads * wl.window * wl.total_tokens * wl.head_dim      # Q_win K^T of one pass
         extra = {
