@@ -36,6 +36,9 @@ constexpr float kNegBig = -1.0e30f;
 
 template <bool V> using BoolC = std::integral_constant<bool, V>;
 template <int V> using IntC = std::integral_constant<int, V>;
+// a ring slot is either a compile-time number (key loop unrolled over the slots) or a run-time one
+template <int V> __device__ __forceinline__ constexpr int slot_of(IntC<V>) { return V; }
+__device__ __forceinline__ constexpr int slot_of(int v) { return v; }
 
 // round-to-nearest-even bf16 bits of a finite float (or of +-inf)
 __device__ inline uint16_t bf16_bits(float x) {
@@ -176,9 +179,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     const int key = unit / SEGS;
     voff[ii] = (uint32_t)(key * kst + ((unit % SEGS) ^ swz(key)) * 8) * 2u;
   }
-  auto issue_tile = [&](int s_idx) __attribute__((always_inline)) {
+  // (where the key loop is unrolled over the NBUF slots the ring slot is a compile-time number, and slot offsets
+  // fold into the instructions' immediate offsets instead of costing an address addition per LDS read)
+  auto issue_tile = [&](int s_idx, auto slot_tag) __attribute__((always_inline)) {
     const int jbase = key0 + 32 * s_idx;
-    uint8_t* slot = ring + (s_idx % NBUF) * TILE_BYTES + wave * 1024;
+    uint8_t* slot = ring + slot_of(slot_tag) * TILE_BYTES + wave * 1024;
     const uint8_t* gbase = reinterpret_cast<const uint8_t*>(kg + (int64_t)jbase * kst);   // wave-uniform
     if (jbase + 32 <= ni) {
 #pragma unroll
@@ -198,10 +203,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   };
   // Operands of the tile being consumed.  Plain loads: an asm ds_read whose result is waited for by a later
   // asm statement is NOT safe -- the compiler may copy the "loaded" register in between, before the data has
-  // arrived (it did, in the software-pipelined loop below).
+  // arrived (it did, in a software-pipelined variant of the key loop).
   bf16x8 kf[KS];
-  auto read_tile = [&](int s_idx) __attribute__((always_inline)) {
-    const uint8_t* slot = ring + (s_idx % NBUF) * TILE_BYTES;
+  auto read_tile = [&](auto slot_tag) __attribute__((always_inline)) {
+    const uint8_t* slot = ring + slot_of(slot_tag) * TILE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int seg = 2 * ks + lh;
@@ -353,7 +358,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // barrier: a plain s_barrier, not __syncthreads(), whose fence waits for ALL outstanding loads and would drain
   // the ring.  After it everybody's share of tile s is in LDS (each wave waited for its own loads) and everybody
   // is done reading tile s-1's slot, which the next request overwrites.
-  auto tile_ready = [&](int s) __attribute__((always_inline)) {
+  auto tile_ready = [&](int s, auto slot_tag) __attribute__((always_inline)) {
     const int later = min(PD - 1, nsub - 1 - s);
     if (later >= 3) wait_vmcnt<3 * IPW>();
     else if (later == 2) wait_vmcnt<2 * IPW>();
@@ -362,39 +367,58 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (s + PD < nsub) issue_tile(s + PD);
+    if (s + PD < nsub) {
+      if constexpr (std::is_same<decltype(slot_tag), int>::value) issue_tile(s + PD, (s + PD) % NBUF);
+      else issue_tile(s + PD, IntC<(decltype(slot_tag)::value + PD) % NBUF>{});
+    }
   };
   // prologue: request the first PD tiles
-#pragma unroll
-  for (int i = 0; i < PD; ++i)
-    if (i < nsub) issue_tile(i);
-  {
-    // one tile per iteration: row block 1's MFMAs run under row block 0's softmax
-    auto rest_of_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
-      if constexpr (NRB == 2) {
-        mfma_block(acc1, kf, IntC<NRB - 1>{});
-        softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
-        interleave_hint();
-        softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase);
-      } else {
-        softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
-      }
-    };
-    for (int s = 0; s < nsub; ++s) {
-      tile_ready(s);
-      read_tile(s);
-      mfma_block(acc0, kf, IntC<0>{});
-      // the column sums of tile s-2 are added up under those MFMAs, when the wave has nothing else to issue
-      // (parked in iteration s-2; every wave has since waited for the operand reads of tile s-1 and passed the
-      // barrier of tile s)
-      if (s >= 2) flush_colsum(s - 2);
-      const int jbase = key0 + 32 * s;
-      const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
-      if (!masked) rest_of_tile(BoolC<false>{}, jbase);
-      else         rest_of_tile(BoolC<true>{}, jbase);
-      park_colsum(jbase);
+  if (0 < PD && 0 < nsub) issue_tile(0, IntC<0>{});
+  if (1 < PD && 1 < nsub) issue_tile(1, IntC<1 % NBUF>{});
+  if (2 < PD && 2 < nsub) issue_tile(2, IntC<2 % NBUF>{});
+  static_assert(PD <= 3, "prologue written out for up to three tiles ahead");
+  // one tile per step: row block 1's MFMAs run under row block 0's softmax
+  auto rest_of_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
+    if constexpr (NRB == 2) {
+      mfma_block(acc1, kf, IntC<NRB - 1>{});
+      softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
+      interleave_hint();
+      softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase);
+    } else {
+      softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
     }
+  };
+  auto tile_step = [&](int s, auto slot_tag) __attribute__((always_inline)) {
+    tile_ready(s, slot_tag);
+    read_tile(slot_tag);
+    mfma_block(acc0, kf, IntC<0>{});
+    // the column sums of tile s-2 are added up under those MFMAs, when the wave has nothing else to issue
+    // (parked in step s-2; every wave has since waited for the operand reads of tile s-1 and passed the
+    // barrier of tile s)
+    if (s >= 2) flush_colsum(s - 2);
+    const int jbase = key0 + 32 * s;
+    // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
+    const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
+    if (!masked) rest_of_tile(BoolC<false>{}, jbase);
+    else         rest_of_tile(BoolC<true>{}, jbase);
+    park_colsum(jbase);
+  };
+  // Unrolled over the ring slots (-2 %), except in the four-wave pass-2 kernel at d = 128, whose 168 registers
+  // the unrolled loop overflows (spills inside the loop: +30 %).
+  constexpr bool UNROLLED = !(PASS == 2 && NW == 4 && D == 128);
+  if constexpr (UNROLLED) {
+    for (int s0 = 0; s0 < nsub; s0 += NBUF) {
+      tile_step(s0, IntC<0>{});
+      if (s0 + 1 < nsub) tile_step(s0 + 1, IntC<1 % NBUF>{});
+      if constexpr (NBUF == 4) {
+        if (s0 + 2 < nsub) tile_step(s0 + 2, IntC<2 % NBUF>{});
+        if (s0 + 3 < nsub) tile_step(s0 + 3, IntC<3 % NBUF>{});
+      }
+    }
+  } else {
+    for (int s = 0; s < nsub; ++s) tile_step(s, s % NBUF);
   }
+  static_assert(NBUF == 2 || NBUF == 4, "key loop unrolled over the ring slots");
 
   if (PASS == 2) {
     if (NW > 1) {
