@@ -30,6 +30,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;   // operand of v_mfma_f32_32x32x8_bf16_1k
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr float kNegBig = -1.0e30f;
@@ -137,18 +138,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rb][ks]));
 
-  // pass 2: the extra k-step.  Query side: -(lse2[row]/c2) in three bf16 pieces (lane half 0, first
-  // three k slots); key side: ones in the same slots.  Padded rows carry -inf, so their p is exactly 0.
-  bf16x8 qaug[PASS == 2 ? NRB : 1] = {};
-  bf16x8 kaug = {};
+  // pass 2: the extra k-step, a v_mfma_f32_32x32x8_bf16_1k (half the registers and half the matrix-pipe time
+  // of a 32x32x16 step; lane l holds row/column l%32 and k = 4(l/32)..+3).  Query side: -(lse2[row]/c2) in three
+  // bf16 pieces (lane half 0, first three k slots); key side: ones in the same slots.  Padded rows carry -inf,
+  // so their p is exactly 0.
+  s16x4 qaug[PASS == 2 ? NRB : 1] = {};
+  s16x4 kaug = {0, 0, 0, 0};
   if (PASS == 2) {
-    u16x8 one = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (lh == 0) { one[0] = 0x3F80; one[1] = 0x3F80; one[2] = 0x3F80; }
-    kaug = __builtin_bit_cast(bf16x8, one);
+    if (lh == 0) { kaug[0] = 0x3F80; kaug[1] = 0x3F80; kaug[2] = 0x3F80; }
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
       const int row = rc * RPC + rb * 32 + l32;
-      u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      s16x4 v = {0, 0, 0, 0};
       if (lh == 0) {
         if (row < R) {
           const float lam = -lse2[(int64_t)b * G * R + (int64_t)g * R + row] / c2;
@@ -156,12 +157,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
           const float r1 = lam - bf16_value(hi);
           const uint16_t mid = bf16_bits(r1);
           const uint16_t lo = bf16_bits(r1 - bf16_value(mid));
-          v[0] = hi; v[1] = mid; v[2] = lo;
+          v[0] = (short)hi; v[1] = (short)mid; v[2] = (short)lo;
         } else {
-          v[0] = 0xFF80;   // -inf
+          v[0] = (short)0xFF80;   // -inf
         }
       }
-      qaug[rb] = __builtin_bit_cast(bf16x8, v);
+      qaug[rb] = v;
       asm volatile("" : "+v"(qaug[rb]));
     }
   }
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       if (PASS == 1) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], acc, 0, 0, 0);
       else           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf[ks], acc, 0, 0, 0);
     }
-    if constexpr (PASS == 2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qaug[rb], kaug, acc, 0, 0, 0);
+    if constexpr (PASS == 2) acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(qaug[rb], kaug, acc, 0, 0, 0);
   };
 
   // softmax arithmetic of one row block against the 32 keys starting at jbase
