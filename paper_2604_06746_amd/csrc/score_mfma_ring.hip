@@ -313,19 +313,29 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   const uint32_t csout_lds = __builtin_amdgcn_groupstaticsize();   // dynamic LDS starts where the static part ends
   const uint32_t csbuf_lds = csout_lds + (uint32_t)KCAP * 4u;
   auto flush_colsum = [&](int s_idx) __attribute__((always_inline)) {
-    if (PASS == 2 && NW > 1 && wave == (s_idx % NW) && lh == 0) {
+    if constexpr (PASS == 2 && NW > 1) if (wave == (s_idx % NW) && lh == 0) {
       // (scalar part of each address through readfirstlane: it stays in a scalar register and is added to the
       // lane part at the point of use, instead of becoming one more loop-carried vector register)
       const uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(((s_idx % 4) * NW) * 256))) + lane_x4_lo;
-      // reads AND their wait in one asm statement each (nothing can get between a read and its wait)
+      // all reads AND their wait in ONE asm statement (nothing can get between a read and its wait; one LDS
+      // round trip for the lot)
       float lo[NW], hi[NW];
-#define SKV_RD(WV)                                                                                             \
-      asm volatile("ds_read_b32 %0, %2 offset:%3\n\tds_read_b32 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"      \
-                   : "=&v"(lo[WV]), "=&v"(hi[WV]) : "v"(a), "n"((WV) * 256), "n"((WV) * 256 + 128))
-      SKV_RD(0);
-      if constexpr (NW > 1) { SKV_RD(1); }
-      if constexpr (NW > 2) { SKV_RD(2); SKV_RD(3); }
-#undef SKV_RD
+      if constexpr (NW == 4) {
+        asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:128\n\t"
+                     "ds_read_b32 %2, %8 offset:256\n\tds_read_b32 %3, %8 offset:384\n\t"
+                     "ds_read_b32 %4, %8 offset:512\n\tds_read_b32 %5, %8 offset:640\n\t"
+                     "ds_read_b32 %6, %8 offset:768\n\tds_read_b32 %7, %8 offset:896\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo[0]), "=&v"(hi[0]), "=&v"(lo[1]), "=&v"(hi[1]), "=&v"(lo[2]), "=&v"(hi[2]),
+                       "=&v"(lo[NW - 1]), "=&v"(hi[NW - 1])
+                     : "v"(a));
+      } else {
+        asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:128\n\t"
+                     "ds_read_b32 %2, %4 offset:256\n\tds_read_b32 %3, %4 offset:384\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(lo[0]), "=&v"(hi[0]), "=&v"(lo[NW - 1]), "=&v"(hi[NW - 1])
+                     : "v"(a));
+      }
       // a wave's sum of a key = its lower lane half's + its upper lane half's; then the waves in order
       float cs = lo[0] + hi[0];
 #pragma unroll
