@@ -138,8 +138,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rb][ks]));
 
-  // pass 2: the extra k-step, a v_mfma_f32_32x32x8_bf16_1k (half the registers and half the matrix-pipe time
-  // of a 32x32x16 step; lane l holds row/column l%32 and k = 4(l/32)..+3).  Query side: -(lse2[row]/c2) in three
+  // pass 2: the extra k-step, a v_mfma_f32_32x32x8_bf16_1k (half the operand registers of a 32x32x16 step;
+  // lane l holds row/column l%32 and k = 4(l/32)..+3).  Query side: -(lse2[row]/c2) in three
   // bf16 pieces (lane half 0, first three k slots); key side: ones in the same slots.  Padded rows carry -inf,
   // so their p is exactly 0.
   s16x4 qaug[PASS == 2 ? NRB : 1] = {};
