@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   const int l32 = lane & 31, lh = lane >> 5;
 
   // workgroup -> (KV head g, group of row-chunks, key chunk); wave -> row-chunk inside the group
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // a scalar: addresses built from it stay in SGPRs
   const int rcg = (RC + NW - 1) / NW;
   // groups that share a K head (kshare > 1) get workgroup numbers a multiple of G/kshare apart: with the
   // usual eight KV heads they run on the same XCD at about the same time, and its L2 serves the re-reads
@@ -312,29 +312,33 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   const uint32_t lane_x4_lo = (uint32_t)l32 * 4u, thread_x4 = (uint32_t)threadIdx.x * 4u;
   const uint32_t csout_lds = __builtin_amdgcn_groupstaticsize();   // dynamic LDS starts where the static part ends
   const uint32_t csbuf_lds = csout_lds + (uint32_t)KCAP * 4u;
-  auto flush_colsum = [&](int s_idx) __attribute__((always_inline)) {
+  // `ring_slot`: s_idx mod 4, a compile-time number where the key loop is unrolled (the slot's offset is then an
+  // immediate of the LDS instructions and costs no register), else a run-time one (its scalar part goes through
+  // readfirstlane, stays in a scalar register and is added to the lane part at the point of use).
+  auto flush_colsum = [&](int s_idx, auto ring_slot) __attribute__((always_inline)) {
     if constexpr (PASS == 2 && NW > 1) if (wave == (s_idx % NW) && lh == 0) {
-      // (scalar part of each address through readfirstlane: it stays in a scalar register and is added to the
-      // lane part at the point of use, instead of becoming one more loop-carried vector register)
-      const uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(((s_idx % 4) * NW) * 256))) + lane_x4_lo;
+      constexpr bool RT = std::is_same<decltype(ring_slot), int>::value;
+      uint32_t a = csbuf_lds + lane_x4_lo;
+      if constexpr (RT) a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(ring_slot * NW * 256))) + lane_x4_lo;
+      constexpr int OFF = RT ? 0 : slot_of(decltype(ring_slot){}) * NW * 256;
       // all reads AND their wait in ONE asm statement (nothing can get between a read and its wait; one LDS
       // round trip for the lot)
       float lo[NW], hi[NW];
       if constexpr (NW == 4) {
-        asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:128\n\t"
-                     "ds_read_b32 %2, %8 offset:256\n\tds_read_b32 %3, %8 offset:384\n\t"
-                     "ds_read_b32 %4, %8 offset:512\n\tds_read_b32 %5, %8 offset:640\n\t"
-                     "ds_read_b32 %6, %8 offset:768\n\tds_read_b32 %7, %8 offset:896\n\t"
+        asm volatile("ds_read_b32 %0, %8 offset:%9\n\tds_read_b32 %1, %8 offset:%9+128\n\t"
+                     "ds_read_b32 %2, %8 offset:%9+256\n\tds_read_b32 %3, %8 offset:%9+384\n\t"
+                     "ds_read_b32 %4, %8 offset:%9+512\n\tds_read_b32 %5, %8 offset:%9+640\n\t"
+                     "ds_read_b32 %6, %8 offset:%9+768\n\tds_read_b32 %7, %8 offset:%9+896\n\t"
                      "s_waitcnt lgkmcnt(0)"
                      : "=&v"(lo[0]), "=&v"(hi[0]), "=&v"(lo[1]), "=&v"(hi[1]), "=&v"(lo[2]), "=&v"(hi[2]),
                        "=&v"(lo[NW - 1]), "=&v"(hi[NW - 1])
-                     : "v"(a));
+                     : "v"(a), "n"(OFF));
       } else {
-        asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:128\n\t"
-                     "ds_read_b32 %2, %4 offset:256\n\tds_read_b32 %3, %4 offset:384\n\t"
+        asm volatile("ds_read_b32 %0, %4 offset:%5\n\tds_read_b32 %1, %4 offset:%5+128\n\t"
+                     "ds_read_b32 %2, %4 offset:%5+256\n\tds_read_b32 %3, %4 offset:%5+384\n\t"
                      "s_waitcnt lgkmcnt(0)"
                      : "=&v"(lo[0]), "=&v"(hi[0]), "=&v"(lo[NW - 1]), "=&v"(hi[NW - 1])
-                     : "v"(a));
+                     : "v"(a), "n"(OFF));
       }
       // a wave's sum of a key = its lower lane half's + its upper lane half's; then the waves in order
       float cs = lo[0] + hi[0];
@@ -349,7 +353,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // pass 2: park this tile's column sums.  ONE store in the loop body, outside the masked / unmasked variants
   // of sub_tile: two copies get merged by the compiler into a store that has lost its alias information, and it
   // then waits for every outstanding tile load (which also write LDS) before it.
-  auto park_colsum = [&](int jbase) __attribute__((always_inline)) {
+  auto park_colsum = [&](int jbase, auto ring_slot) __attribute__((always_inline)) {
     if (PASS == 2) {
       float cs = cs0 + cs1;
       if (NW == 1) {
@@ -358,9 +362,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
           asm volatile("ds_write_b32 %0, %1" : : "v"(csout_lds + (uint32_t)((jbase - key0 + l32) * 4)), "v"(cs) : "memory");
       } else {
         // both lane halves park their sums: no cross-lane exchange in the key loop
-        const uint32_t a = (uint32_t)__builtin_amdgcn_readfirstlane(
-                               (int)(csbuf_lds + (uint32_t)(((((jbase - key0) >> 5) % 4) * NW) * 256))) + thread_x4;
-        asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(live ? cs : 0.f) : "memory");
+        constexpr bool RT = std::is_same<decltype(ring_slot), int>::value;
+        uint32_t a = csbuf_lds + thread_x4;
+        if constexpr (RT) a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(ring_slot * NW * 256))) + thread_x4;
+        constexpr int OFF = RT ? 0 : slot_of(decltype(ring_slot){}) * NW * 256;
+        asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(a), "v"(live ? cs : 0.f), "n"(OFF) : "memory");
       }
       cs0 = 0.f; cs1 = 0.f;
     }
@@ -406,29 +412,29 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     // the column sums of tile s-2 are added up under those MFMAs, when the wave has nothing else to issue
     // (parked in step s-2; every wave has since waited for the operand reads of tile s-1 and passed the
     // barrier of tile s)
-    if (s >= 2) flush_colsum(s - 2);
+    if (s >= 2) {
+      if constexpr (std::is_same<decltype(slot_tag), int>::value) flush_colsum(s - 2, (s - 2) % 4);
+      else flush_colsum(s - 2, IntC<(decltype(slot_tag)::value + 2) % 4>{});
+    }
     const int jbase = key0 + 32 * s;
     // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
     const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
     if (!masked) rest_of_tile(BoolC<false>{}, jbase);
     else         rest_of_tile(BoolC<true>{}, jbase);
-    park_colsum(jbase);
+    if constexpr (std::is_same<decltype(slot_tag), int>::value) park_colsum(jbase, s % 4);
+    else park_colsum(jbase, slot_tag);
   };
-  // Unrolled over the ring slots (-2 %), except in the four-wave pass-2 kernel at d = 128, whose 168 registers
-  // the unrolled loop overflows (spills inside the loop: +30 %).
-  constexpr bool UNROLLED = !(PASS == 2 && NW == 4 && D == 128);
-  if constexpr (UNROLLED) {
-    for (int s0 = 0; s0 < nsub; s0 += NBUF) {
-      tile_step(s0, IntC<0>{});
-      if (s0 + 1 < nsub) tile_step(s0 + 1, IntC<1 % NBUF>{});
-      if constexpr (NBUF == 4) {
-        if (s0 + 2 < nsub) tile_step(s0 + 2, IntC<2 % NBUF>{});
-        if (s0 + 3 < nsub) tile_step(s0 + 3, IntC<3 % NBUF>{});
-      }
+  // unrolled over the ring slots (-2 %): a tile's ring slot, and with four slots its column-sum slot (tile mod 4),
+  // are compile-time numbers inside a step
+  for (int s0 = 0; s0 < nsub; s0 += NBUF) {
+    tile_step(s0, IntC<0>{});
+    if (s0 + 1 < nsub) tile_step(s0 + 1, IntC<1 % NBUF>{});
+    if constexpr (NBUF == 4) {
+      if (s0 + 2 < nsub) tile_step(s0 + 2, IntC<2 % NBUF>{});
+      if (s0 + 3 < nsub) tile_step(s0 + 3, IntC<3 % NBUF>{});
     }
-  } else {
-    for (int s = 0; s < nsub; ++s) tile_step(s, s % NBUF);
   }
+  static_assert(NW == 1 || NBUF == 4, "the parked column sums use the ring slot number as tile mod 4");
   static_assert(NBUF == 2 || NBUF == 4, "key loop unrolled over the ring slots");
 
   if (PASS == 2) {
@@ -438,7 +444,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       __syncthreads();
 #pragma unroll
       for (int t = 3; t >= 1; --t)
-        if (nsub >= t) flush_colsum(nsub - t);   // (the oldest of the three may have been added up already)
+        if (nsub >= t) flush_colsum(nsub - t, (nsub - t) % 4);   // (the oldest of the three may have been added up already)
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __syncthreads();
