@@ -16,8 +16,9 @@
 //     tiles ahead, into an XOR-swizzled layout that makes the operand reads bank-conflict free;
 //   * inside a wave the MFMAs of row block rb+1 are issued under the softmax arithmetic of row block rb.
 //
-//   pass 1:  S^T = K Q^T   a lane owns ONE query row of each row block and 16 keys: running
-//            M = max x, Z = sum 2^(x-M), E = sum 2^(x-M)(x-M) per row, x = c2 (q.k), c2 = scale log2(e)
+//   pass 1:  S^T = K Q^T   a lane owns ONE query row of each row block and 16 keys: a reference M (the maximum
+//            of the chunk's first tile; the running maximum in the rare rerun), Z = sum 2^(x-M),
+//            E = sum 2^(x-M)(x-M) per row, x = c2 (q.k), c2 = scale log2(e)
 //   pass 2:  S = Q K^T     a lane owns ONE key and 16 rows of each row block; -lse2[row]/c2 rides in
 //            one extra MFMA k-step (three bf16 pieces of it against ones on the key side), so
 //            p = 2^(c2 acc) needs no per-row constant in registers; the lane sums its key's column.
@@ -239,9 +240,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   };
 
   // softmax arithmetic of one row block against the 32 keys starting at jbase
-  auto softmax_block = [&](auto masked_tag, floatx16& acc, auto rb_tag, int jbase) __attribute__((always_inline)) {
+  // FIXED_REF (pass 1): the row's reference M stays what the chunk's first tile set it to -- no tile maximum, no
+  // rescaling of the running sums (a sixth of the vector instructions).  Any reference gives the same
+  // statistics as long as nothing overflows; whether something came near that is checked after the loop.
+  auto softmax_block = [&](auto masked_tag, floatx16& acc, auto rb_tag, int jbase, auto fixed_tag) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     constexpr int rb = decltype(rb_tag)::value;
+    constexpr bool FIXED_REF = decltype(fixed_tag)::value;
     if (PASS == 1) {
       if (MASKED) {
         const int lim = causal ? ni - w + win[rb] + 1 : ni;
@@ -250,6 +255,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
           const int j = jbase + 8 * (i / 4) + 4 * lh + (i % 4);
           if (j >= lim) acc[i] = -INFINITY;
         }
+      }
+      if constexpr (FIXED_REF) {
+        const float nm = -M[rb];
+        float z0 = Z[rb], z1 = 0.f, e0 = E[rb], e1 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          float ta = fmaf(acc[i], c2, nm);
+          float tb = fmaf(acc[i + 1], c2, nm);
+          if (MASKED) { ta = fmaxf(ta, -200.f); tb = fmaxf(tb, -200.f); }
+          const float pa = __builtin_amdgcn_exp2f(ta);
+          const float pb = __builtin_amdgcn_exp2f(tb);
+          z0 += pa; z1 += pb;
+          e0 = fmaf(pa, ta, e0); e1 = fmaf(pb, tb, e1);
+        }
+        Z[rb] = z0 + z1; E[rb] = e0 + e1;
+        return;
       }
       float tm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
 #pragma unroll
@@ -389,23 +410,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       else issue_tile(s + PD, IntC<(decltype(slot_tag)::value + PD) % NBUF>{});
     }
   };
-  // prologue: request the first PD tiles
-  if (0 < PD && 0 < nsub) issue_tile(0, IntC<0>{});
-  if (1 < PD && 1 < nsub) issue_tile(1, IntC<1 % NBUF>{});
-  if (2 < PD && 2 < nsub) issue_tile(2, IntC<2 % NBUF>{});
-  static_assert(PD <= 3, "prologue written out for up to three tiles ahead");
   // one tile per step: row block 1's MFMAs run under row block 0's softmax
-  auto rest_of_tile = [&](auto masked_tag, int jbase) __attribute__((always_inline)) {
+  auto rest_of_tile = [&](auto masked_tag, int jbase, auto fixed_tag) __attribute__((always_inline)) {
     if constexpr (NRB == 2) {
       mfma_block(acc1, kf, IntC<NRB - 1>{});
-      softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
+      softmax_block(masked_tag, acc0, IntC<0>{}, jbase, fixed_tag);
       interleave_hint();
-      softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase);
+      softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase, fixed_tag);
     } else {
-      softmax_block(masked_tag, acc0, IntC<0>{}, jbase);
+      softmax_block(masked_tag, acc0, IntC<0>{}, jbase, fixed_tag);
     }
   };
-  auto tile_step = [&](int s, auto slot_tag) __attribute__((always_inline)) {
+  // fixed_mode: pass 1 with the fixed reference (every tile but the chunk's first, which sets it)
+  auto tile_step = [&](int s, auto slot_tag, auto fixed_mode) __attribute__((always_inline)) {
     tile_ready(s, slot_tag);
     read_tile(slot_tag);
     mfma_block(acc0, kf, IntC<0>{});
@@ -419,20 +436,58 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     const int jbase = key0 + 32 * s;
     // pass 1 masks the ragged tail and the causal triangle; pass 2 only the causal triangle
     const bool masked = PASS == 1 ? (jbase + 32 > n_full) : (causal && jbase + 32 > n_full);
-    if (!masked) rest_of_tile(BoolC<false>{}, jbase);
-    else         rest_of_tile(BoolC<true>{}, jbase);
+    if (!masked) rest_of_tile(BoolC<false>{}, jbase, fixed_mode);
+    else         rest_of_tile(BoolC<true>{}, jbase, fixed_mode);
     if constexpr (std::is_same<decltype(slot_tag), int>::value) park_colsum(jbase, s % 4);
     else park_colsum(jbase, slot_tag);
   };
-  // unrolled over the ring slots (-2 %): a tile's ring slot, and with four slots its column-sum slot (tile mod 4),
-  // are compile-time numbers inside a step
-  for (int s0 = 0; s0 < nsub; s0 += NBUF) {
-    tile_step(s0, IntC<0>{});
-    if (s0 + 1 < nsub) tile_step(s0 + 1, IntC<1 % NBUF>{});
-    if constexpr (NBUF == 4) {
-      if (s0 + 2 < nsub) tile_step(s0 + 2, IntC<2 % NBUF>{});
-      if (s0 + 3 < nsub) tile_step(s0 + 3, IntC<3 % NBUF>{});
+  // the whole key chunk: prologue (request the first PD tiles), then the loop, unrolled over the ring slots
+  // (-2 %: a tile's ring slot, and with four slots its column-sum slot (tile mod 4), are compile-time numbers
+  // inside a step)
+  auto run_chunk = [&](auto fixed_mode) __attribute__((always_inline)) {
+    if (0 < PD && 0 < nsub) issue_tile(0, IntC<0>{});
+    if (1 < PD && 1 < nsub) issue_tile(1, IntC<1 % NBUF>{});
+    if (2 < PD && 2 < nsub) issue_tile(2, IntC<2 % NBUF>{});
+    // the first tile on its own (it sets the reference when that is fixed), then groups of NBUF tiles
+    if (nsub > 0) tile_step(0, IntC<0>{}, BoolC<false>{});
+    for (int s0 = 0; s0 + 1 < nsub; s0 += NBUF) {
+      tile_step(s0 + 1, IntC<1 % NBUF>{}, fixed_mode);
+      if constexpr (NBUF == 4) {
+        if (s0 + 2 < nsub) tile_step(s0 + 2, IntC<2>{}, fixed_mode);
+        if (s0 + 3 < nsub) tile_step(s0 + 3, IntC<3>{}, fixed_mode);
+      }
+      if (s0 + NBUF < nsub) tile_step(s0 + NBUF, IntC<0>{}, fixed_mode);
     }
+  };
+  static_assert(PD <= 3, "prologue written out for up to three tiles ahead");
+  if constexpr (PASS == 1) {
+    // Fast run with the fixed reference; then a workgroup-wide vote (every wave has to take part in a rerun:
+    // they load the tiles together).  A sum whose exponent shows that some logit lay 2^60 above its row's
+    // reference (or that is inf / NaN) sends the workgroup through the chunk again with the running maximum.
+    const uint32_t flag_lds = __builtin_amdgcn_groupstaticsize();   // one word of dynamic LDS
+    if (threadIdx.x == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(flag_lds), "v"(0) : "memory");
+    run_chunk(BoolC<true>{});
+    bool suspect = false;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      const uint32_t ez = (__float_as_uint(Z[rb]) >> 23) & 0xFFu, ee = (__float_as_uint(E[rb]) >> 23) & 0xFFu;
+      suspect = suspect || ez >= 127u + 60u || ee >= 127u + 66u;
+    }
+    if (nsub > 0) {   // (with no tile there was no barrier either: nothing ran, nothing to vote on)
+      if (__builtin_amdgcn_ballot_w64(suspect) != 0 && lane == 0)
+        asm volatile("ds_write_b32 %0, %1" : : "v"(flag_lds), "v"(1) : "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      int flag;
+      asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(flag) : "v"(flag_lds) : "memory");
+      if (__builtin_amdgcn_readfirstlane(flag) != 0) {
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) { M[rb] = kNegBig; Z[rb] = 0.f; E[rb] = 0.f; }
+        run_chunk(BoolC<false>{});
+      }
+    }
+  } else {
+    run_chunk(BoolC<false>{});
   }
   static_assert(NW == 1 || NBUF == 4, "the parked column sums use the ring slot number as tile mod 4");
   static_assert(NBUF == 2 || NBUF == 4, "key loop unrolled over the ring slots");
@@ -485,7 +540,7 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
   dim3 g((unsigned)grid), blk(64 * NW);
   // pass 2: dynamic LDS for the column sums of the key chunk and the waves' parked sums
   const unsigned cs_bytes = (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
-  const unsigned dyn = pass == 1 ? 0u : cs_bytes;
+  const unsigned dyn = pass == 1 ? 16u : cs_bytes;   // pass 1: the word of the rerun vote
 #define SKV_ARGS                                                                                        \
   g, blk, dyn, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
       s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs

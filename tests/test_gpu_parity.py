@@ -154,6 +154,28 @@ def test_score_layer_strided_k_and_explicit_scale(B, sweep_mod, oracle):
     assert_entropy(sw.entropy.cpu().numpy(), ent, 1e-3)
 
 
+@pytest.mark.parametrize("name", ["s_bf16_w64", "s_bf16_gqa4", "s_bf16_r64"])
+def test_late_dominant_keys_rerun_with_running_maximum(sweep_mod, oracle, name):
+    # Pass 1 keeps the reference its chunk's FIRST tile set; keys far above it later in the chunk push the sums
+    # towards overflow, which the kernel must notice and answer with a rerun under the running maximum.
+    # Here every key from 40 % of the sequence on is 24 x larger (logits up to a few hundred above the early ones).
+    wl = workloads.WORKLOADS[name]
+    x = workloads.make_layer(wl, 0, "cuda")
+    n = wl.seq_lens[0]
+    k = x.k.clone()
+    k[:, int(0.4 * n):, :] *= 24.0
+    sw = make_sweep(sweep_mod, wl)
+    sw.score(x.q_win, k)
+    torch.cuda.synchronize()
+    D, ent, ent_h, _ = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(k), wl.n_q_heads, wl.n_kv_heads,
+                                          wl.head_dim, wl.window, wl.seq_lens)
+    got = sw.indeg.cpu().numpy()
+    assert np.isfinite(got).all() and abs(got.sum() - wl.window * wl.n_q_heads) < 1e-2
+    assert_close_floor(got, D, 1e-3, "in-degree with late dominant keys")
+    assert_entropy(sw.entropy.cpu().numpy(), ent, 1e-3)
+    assert_entropy(sw.entropy_per_head.cpu().numpy().ravel(), ent_h.ravel(), 1e-3)
+
+
 def test_uniform_attention_entropy_is_log_n(sweep_mod):
     # all keys identical -> every row is uniform: D_j = w*H_q/n and entropy = ln n
     n, Hq, G, d, w = 1500, 8, 2, 128, 32
