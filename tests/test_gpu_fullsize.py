@@ -51,6 +51,47 @@ def test_headline_config_whole_sweep(sweep_mod, oracle):
     torch.cuda.empty_cache()
 
 
+def test_headline_graph_with_side_stream_equals_eager(sweep_mod):
+    # bench.py's launch configuration at full size (four layers of it): the sweep captured in a HIP graph with
+    # selection + gather on a side stream, replayed twice, against plain eager launches -- same bits
+    from helpers import make_sweep
+    wl = workloads.C3_128K
+    L = 4
+    layers = [workloads.make_layer(wl, l, "cuda") for l in range(L)]
+    ref = make_sweep(sweep_mod, wl, n_layers_out=L)
+    for l, x in enumerate(layers):
+        ref.layer(x.q_win, x.k, x.v, slot=l)
+    ref.select_struct()
+    torch.cuda.synchronize()
+    sw = make_sweep(sweep_mod, wl, n_layers_out=L)
+    side = torch.cuda.Stream()
+
+    def step():
+        sw.reset()
+        sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
+        sw.select_struct()
+
+    warm = torch.cuda.Stream()
+    warm.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(warm):
+        step()
+    torch.cuda.current_stream().wait_stream(warm)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(2):
+        sw.indeg.fill_(-1.0); sw.idx_kv.fill_(-1); sw.k_cache.zero_(); sw.centrality.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ref.centrality, sw.centrality) and torch.equal(ref.idx_struct, sw.idx_struct), rep
+        assert torch.equal(ref.idx_kv, sw.idx_kv), rep
+        assert torch.equal(ref.k_cache, sw.k_cache) and torch.equal(ref.v_cache, sw.v_cache), rep
+    del graph, layers
+    torch.cuda.empty_cache()
+
+
 def test_pivot_metrics_at_32k(sweep_mod, oracle):
     # Eq. 5-6 on one layer of the 32K configuration against the oracle's attention rows (268 MB of fp64)
     from paper_2604_06746_amd import binding as B

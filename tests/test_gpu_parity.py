@@ -621,3 +621,51 @@ def test_overlapped_sweep_equals_sequential(sweep_mod):
     assert torch.equal(seq.centrality, ovl.centrality)
     assert torch.equal(seq.k_cache, ovl.k_cache) and torch.equal(seq.v_cache, ovl.v_cache)
     assert torch.equal(seq.idx_kv, ovl.idx_kv)
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
+    # the launch configuration bench.py times: the whole sweep captured once in a HIP graph (one stream, or with
+    # selection + gather on a side stream) and replayed.  Every replay must give the eager sweep's bits; eager work
+    # and synchronisations sit between the replays, and the inputs change between them.
+    wl = workloads.S_BF16_W64
+    L = 4
+    layers = [workloads.make_layer(wl, l % wl.n_layers, "cuda") for l in range(L)]
+    ref = make_sweep(sweep_mod, wl, n_layers_out=L)
+    sw = make_sweep(sweep_mod, wl, n_layers_out=L)
+    side = torch.cuda.Stream() if overlap else None
+
+    def sweep_on(obj):
+        obj.reset()
+        if overlap and obj is sw:
+            obj.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
+        else:
+            for l, x in enumerate(layers):
+                obj.layer(x.q_win, x.k, x.v, slot=l)
+        obj.select_struct()
+
+    warm = torch.cuda.Stream()
+    warm.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(warm):
+        sweep_on(sw)                                     # every kernel once outside capture
+    torch.cuda.current_stream().wait_stream(warm)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sweep_on(sw)
+    for rep in range(3):
+        if rep:                                          # new inputs in the same buffers, some eager work in between
+            for x in layers:
+                x.k.mul_(1.0 + 0.25 * rep)
+                x.q_win.add_(0.125 * rep)
+            sw.indeg.fill_(-1.0); sw.idx_kv.fill_(-1); sw.k_cache.zero_()
+            torch.cuda.synchronize()
+        sweep_on(ref)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ref.centrality, sw.centrality), rep
+        assert torch.equal(ref.idx_kv, sw.idx_kv) and torch.equal(ref.idx_struct, sw.idx_struct), rep
+        assert torch.equal(ref.k_cache, sw.k_cache) and torch.equal(ref.v_cache, sw.v_cache), rep
+        assert torch.equal(ref.entropy, sw.entropy), rep
+
