@@ -31,9 +31,10 @@ def parse_args():
     ap.add_argument("--workload", default="c3_llama8b_128k")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the sweep is captured once in a HIP graph and replayed per step")
-    ap.add_argument("--overlap", type=int, default=1,
-                    help="1 (default): selection + gather of layer l run on a side stream (default priority) under "
-                         "the scoring of layer l+1, same results bit for bit, ~7 %% faster; 0: one stream")
+    ap.add_argument("--overlap", type=int, default=2,
+                    help="2 (default): two chains of alternate layers on two streams (default priority), the "
+                         "recurrence kept in layer order by events; 1: selection + gather of layer l on a side "
+                         "stream under the scoring of layer l+1; 0: one stream.  Same results bit for bit.")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
     ap.add_argument("--cpu-sample-layers", type=int, default=32, help="layers the CPU oracle is timed on (0 = skip)")
     return ap.parse_args()
@@ -66,7 +67,9 @@ def main():
 
     def step():
         sw.reset()
-        if side_stream is not None:
+        if args.overlap == 2:
+            sw.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side_stream)
+        elif side_stream is not None:
             sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side_stream)
         else:
             for l in range(L):
@@ -225,7 +228,9 @@ def main():
         "config": {"workload": wl.name, "layers": L, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_lens": list(wl.seq_lens) if wl.batch > 1 else wl.seq_lens[0],
                    "window": wl.window, "k": list(wl.k_per_seq) if wl.batch > 1 else wl.k_per_seq[0],
-                   "launch": mode, "streams": 2 if args.overlap else 1},
+                   "launch": mode, "streams": 2 if args.overlap else 1,
+                   "stream_plan": {0: "one stream", 1: "selection and gather on a side stream",
+                                   2: "two chains of alternate layers"}[args.overlap]},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     out.update(extra)

@@ -51,9 +51,11 @@ def test_headline_config_whole_sweep(sweep_mod, oracle):
     torch.cuda.empty_cache()
 
 
-def test_headline_graph_with_side_stream_equals_eager(sweep_mod):
-    # bench.py's launch configuration at full size (four layers of it): the sweep captured in a HIP graph with
-    # selection + gather on a side stream, replayed twice, against plain eager launches -- same bits
+@pytest.mark.parametrize("chains", [False, True])
+def test_headline_graph_with_two_streams_equals_eager(sweep_mod, chains):
+    # bench.py's launch configuration at full size (four layers of it): the sweep captured in a HIP graph on two
+    # streams (two chains of alternate layers, or selection + gather on a side stream), replayed twice, against
+    # plain eager launches -- same bits
     from helpers import make_sweep
     wl = workloads.C3_128K
     L = 4
@@ -68,7 +70,10 @@ def test_headline_graph_with_side_stream_equals_eager(sweep_mod):
 
     def step():
         sw.reset()
-        sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
+        if chains:
+            sw.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
+        else:
+            sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
         sw.select_struct()
 
     warm = torch.cuda.Stream()

@@ -623,10 +623,33 @@ def test_overlapped_sweep_equals_sequential(sweep_mod):
     assert torch.equal(seq.idx_kv, ovl.idx_kv)
 
 
-@pytest.mark.parametrize("overlap", [False, True])
+@pytest.mark.parametrize("L", [1, 4, 5])
+def test_two_chain_sweep_equals_sequential(sweep_mod, L):
+    # even layers on one stream, odd layers on another, the recurrence kept in layer order by events: same bits
+    wl = workloads.S_BF16_RAGGED
+    layers = [workloads.make_layer(wl, l % wl.n_layers, "cuda") for l in range(L)]
+    for l, x in enumerate(layers):
+        x.k.mul_(1.0 + 0.1 * l)                          # every layer different, so a swapped order would show
+    seq = make_sweep(sweep_mod, wl, n_layers_out=L)
+    for l, x in enumerate(layers):
+        seq.layer(x.q_win, x.k, x.v, slot=l)
+    torch.cuda.synchronize()
+    two = make_sweep(sweep_mod, wl, n_layers_out=L)
+    side = torch.cuda.Stream()
+    for _ in range(2):                                   # twice: buffers are reused across sweeps
+        two.reset()
+        two.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
+    torch.cuda.synchronize()
+    assert torch.equal(seq.centrality, two.centrality)
+    assert torch.equal(seq.k_cache, two.k_cache) and torch.equal(seq.v_cache, two.v_cache)
+    assert torch.equal(seq.idx_kv, two.idx_kv) and torch.equal(seq.indeg, two.indeg)
+    assert torch.equal(seq.entropy, two.entropy) and torch.equal(seq.entropy_per_head, two.entropy_per_head)
+
+
+@pytest.mark.parametrize("overlap", [0, 1, 2])
 def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
-    # the launch configuration bench.py times: the whole sweep captured once in a HIP graph (one stream, or with
-    # selection + gather on a side stream) and replayed.  Every replay must give the eager sweep's bits; eager work
+    # the launch configuration bench.py times: the whole sweep captured once in a HIP graph (one stream, selection +
+    # gather on a side stream, or two chains of alternate layers) and replayed.  Every replay must give the eager sweep's bits; eager work
     # and synchronisations sit between the replays, and the inputs change between them.
     wl = workloads.S_BF16_W64
     L = 4
@@ -637,8 +660,10 @@ def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
 
     def sweep_on(obj):
         obj.reset()
-        if overlap and obj is sw:
+        if overlap == 1 and obj is sw:
             obj.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
+        elif overlap == 2 and obj is sw:
+            obj.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
         else:
             for l, x in enumerate(layers):
                 obj.layer(x.q_win, x.k, x.v, slot=l)
