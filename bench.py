@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the sweep is captured once in a HIP graph and replayed per step")
     ap.add_argument("--overlap", type=int, default=2,
-                    help="2 (default): two chains of alternate layers on two streams (default priority), the "
+                    help="N >= 2 (default 2): N chains of layers, layer l on stream l mod N (default priority), the "
                          "recurrence kept in layer order by events; 1: selection + gather of layer l on a side "
                          "stream under the scoring of layer l+1; 0: one stream.  Same results bit for bit.")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
@@ -63,12 +63,13 @@ def main():
     sw = sweep_mod.LayerSweep(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.torch_dtype,
                               wl.seq_lens, wl.k_per_seq, lam=wl.lam, n_layers_out=L)
 
-    side_stream = torch.cuda.Stream() if args.overlap else None   # default priority
+    side_streams = [torch.cuda.Stream() for _ in range(max(args.overlap - 1, 1 if args.overlap else 0))]   # default priority
+    side_stream = side_streams[0] if side_streams else None
 
     def step():
         sw.reset()
-        if args.overlap == 2:
-            sw.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side_stream)
+        if args.overlap >= 2:
+            sw.sweep_chains(((x.q_win, x.k, x.v) for x in layers), side_streams)
         elif side_stream is not None:
             sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side_stream)
         else:
@@ -228,9 +229,9 @@ def main():
         "config": {"workload": wl.name, "layers": L, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_lens": list(wl.seq_lens) if wl.batch > 1 else wl.seq_lens[0],
                    "window": wl.window, "k": list(wl.k_per_seq) if wl.batch > 1 else wl.k_per_seq[0],
-                   "launch": mode, "streams": 2 if args.overlap else 1,
-                   "stream_plan": {0: "one stream", 1: "selection and gather on a side stream",
-                                   2: "two chains of alternate layers"}[args.overlap]},
+                   "launch": mode, "streams": max(args.overlap, 2) if args.overlap else 1,
+                   "stream_plan": {0: "one stream", 1: "selection and gather on a side stream"}.get(
+                       args.overlap, "%d chains of layers, one stream each" % args.overlap)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     out.update(extra)

@@ -102,38 +102,40 @@ class LayerSweep:
         self.select_kv(stream)
         self.gather(k, v, slot, stream)
 
-    def _second_chain(self):
-        """Buffers of the second chain of sweep_two_chains (allocated on first use)."""
-        if getattr(self, "_chain", None) is None:
-            dev = self.centrality.device
-            mk = lambda t: torch.empty_like(t)
-            self._chain = [
-                dict(ws=self.workspace, tws=self.topk_workspace, indeg=self._indeg2[0], idx=self.idx_kv,
-                     ent=self.entropy, enth=self.entropy_per_head),
-                dict(ws=mk(self.workspace), tws=mk(self.topk_workspace), indeg=self._indeg2[1], idx=mk(self.idx_kv),
-                     ent=mk(self.entropy), enth=mk(self.entropy_per_head)),
-            ]
-        return self._chain
+    def _chains(self, n: int):
+        """Per-chain buffers of sweep_chains (chain 0 uses the sweep's own; the others are allocated on first use)."""
+        chains = getattr(self, "_chain_bufs", None)
+        if chains is None:
+            chains = self._chain_bufs = [dict(ws=self.workspace, tws=self.topk_workspace, indeg=self._indeg2[0],
+                                              idx=self.idx_kv, ent=self.entropy, enth=self.entropy_per_head)]
+        mk = torch.empty_like
+        while len(chains) < n:
+            indeg = self._indeg2[1] if len(chains) == 1 else mk(self._indeg2[0])
+            chains.append(dict(ws=mk(self.workspace), tws=mk(self.topk_workspace), indeg=indeg, idx=mk(chains[0]["idx"]),
+                               ent=mk(chains[0]["ent"]), enth=mk(chains[0]["enth"])))
+        return chains
 
-    def sweep_two_chains(self, layers, stream_b, slots=None) -> None:
-        """All layers of a prefill as two chains: even layers on the current stream, odd layers on `stream_b`,
-        each as score -> accumulate -> select -> gather with buffers of its own.  Layers are independent except for
-        the recurrence C <- lambda C + D/w, which events keep in layer order, so the results are those of layer()
-        in a loop, bit for bit; one chain's short kernels run under the other chain's scoring kernels.
-        Afterwards indeg / idx_kv / entropy / entropy_per_head are the LAST layer's.  Ends with both streams joined
-        on the current one."""
+    def sweep_chains(self, layers, other_streams, slots=None) -> None:
+        """All layers of a prefill as 1 + len(other_streams) chains: layer l runs on chain l mod n -- chain 0 is the
+        current stream -- as score -> accumulate -> select -> gather with the chain's own buffers.  Layers are
+        independent except for the recurrence C <- lambda C + D/w, which events keep in layer order, so the
+        results are those of layer() in a loop, bit for bit; one chain's short kernels run under another chain's
+        scoring kernels.  Afterwards indeg / idx_kv / entropy / entropy_per_head are the LAST layer's.  Ends with
+        all streams joined on the current one."""
         a = torch.cuda.current_stream()
-        chain = self._second_chain()
+        streams = [a] + list(other_streams)
+        n = len(streams)
+        chain = self._chains(n)
         start = torch.cuda.Event()
         start.record(a)
-        stream_b.wait_event(start)
+        for st in streams[1:]:
+            st.wait_event(start)
         acc_done = None
         last = 0
         for l, (q_win, k, v) in enumerate(layers):
-            c = chain[l & 1]
-            st = a if (l & 1) == 0 else stream_b
+            c, st = chain[l % n], streams[l % n]
             B.structkv_score_layer(self.shape, q_win, k, self.cu, c["indeg"], c["ent"], c["enth"], c["ws"], st)
-            if acc_done is not None:
+            if acc_done is not None and n > 1:
                 st.wait_event(acc_done)
             B.structkv_accumulate_centrality(self.centrality, c["indeg"], self.lam, 1.0 / self.w, st)
             acc_done = torch.cuda.Event()
@@ -142,12 +144,17 @@ class LayerSweep:
             slot = l if slots is None else slots[l]
             B.structkv_gather_kv(k, v, self.k_cache[slot], self.v_cache[slot], self.cu, self.rows_per_seq,
                                  c["idx"], st)
-            last = l & 1
-        done = torch.cuda.Event()
-        done.record(stream_b)
-        a.wait_event(done)
+            last = l % n
+        for st in streams[1:]:
+            done = torch.cuda.Event()
+            done.record(st)
+            a.wait_event(done)
         c = chain[last]
         self.indeg, self.idx_kv, self.entropy, self.entropy_per_head = c["indeg"], c["idx"], c["ent"], c["enth"]
+
+    def sweep_two_chains(self, layers, stream_b, slots=None) -> None:
+        """sweep_chains with two chains: even layers on the current stream, odd layers on `stream_b`."""
+        self.sweep_chains(layers, [stream_b], slots)
 
     def sweep_overlapped(self, layers, side_stream, slots=None) -> None:
         """All layers of a prefill: the scoring chain (score -> accumulate) of layer l+1 runs on the current

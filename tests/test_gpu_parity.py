@@ -623,9 +623,9 @@ def test_overlapped_sweep_equals_sequential(sweep_mod):
     assert torch.equal(seq.idx_kv, ovl.idx_kv)
 
 
-@pytest.mark.parametrize("L", [1, 4, 5])
-def test_two_chain_sweep_equals_sequential(sweep_mod, L):
-    # even layers on one stream, odd layers on another, the recurrence kept in layer order by events: same bits
+@pytest.mark.parametrize("L,chains", [(1, 2), (4, 2), (5, 2), (7, 3)])
+def test_chained_sweep_equals_sequential(sweep_mod, L, chains):
+    # layer l on stream l mod chains, the recurrence kept in layer order by events: same bits
     wl = workloads.S_BF16_RAGGED
     layers = [workloads.make_layer(wl, l % wl.n_layers, "cuda") for l in range(L)]
     for l, x in enumerate(layers):
@@ -635,10 +635,10 @@ def test_two_chain_sweep_equals_sequential(sweep_mod, L):
         seq.layer(x.q_win, x.k, x.v, slot=l)
     torch.cuda.synchronize()
     two = make_sweep(sweep_mod, wl, n_layers_out=L)
-    side = torch.cuda.Stream()
+    sides = [torch.cuda.Stream() for _ in range(chains - 1)]
     for _ in range(2):                                   # twice: buffers are reused across sweeps
         two.reset()
-        two.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
+        two.sweep_chains(((x.q_win, x.k, x.v) for x in layers), sides)
     torch.cuda.synchronize()
     assert torch.equal(seq.centrality, two.centrality)
     assert torch.equal(seq.k_cache, two.k_cache) and torch.equal(seq.v_cache, two.v_cache)
