@@ -21,6 +21,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+# Vector ALU: 256 CUs x 4 SIMDs, one 64-lane instruction per 4 cycles, 2.4 GHz.  v_exp_f32 issues at half that rate
+# on this chip (measured: 8.2 cycles per instruction), so it counts as two slots.
+VALU_PEAK_GSLOTS = 256 * 4 * 2.4 / 4.0
+VALU_SLOTS_PER_LOGIT = {"score_pass1": 5, "score_pass2": 4}   # scale-fma, exp (2), add, fma  /  mul, exp (2), add
 
 
 def parse_args():
@@ -184,11 +188,16 @@ def main():
                     "measured_copy_GBs": round(copy_gbs, 1), "frac_of_measured_copy": round(achieved / copy_gbs, 4)}
         score_us = sum(kern_us[k] for k in names[:4])
         qk_flops = 2.0 * wl.n_q_heads * wl.window * wl.total_tokens * wl.head_dim      # Q_win K^T of one pass
+        # wave-wide vector instruction slots the softmax of one pass needs at least (one lane per logit)
+        valu_slots = VALU_SLOTS_PER_LOGIT[dom] * wl.n_q_heads * wl.window * wl.total_tokens / 64.0
         extra = {
             "mfma": {"kernel": dom, "achieved_TFLOPs": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12, 1),
                      "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
                      "frac": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "flops_per_launch": qk_flops},
+            "valu": {"kernel": dom, "slots_per_logit": VALU_SLOTS_PER_LOGIT[dom],
+                     "achieved_Gslots": round(valu_slots / (kern_us[dom] * 1e-6) / 1e9, 1), "peak_Gslots": VALU_PEAK_GSLOTS,
+                     "frac": round(valu_slots / (kern_us[dom] * 1e-6) / 1e9 / VALU_PEAK_GSLOTS, 4)},
             "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
             "k_stream_both_passes": {"achieved_GBs": round(k_bytes / (score_us * 1e-6) / 1e9, 1),
                                      "frac": round(k_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
