@@ -35,8 +35,8 @@ def parse_args():
     ap.add_argument("--workload", default="c3_llama8b_128k")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="graph: the sweep is captured once in a HIP graph and replayed per step")
-    ap.add_argument("--overlap", type=int, default=2,
-                    help="N >= 2 (default 2): N chains of layers, layer l on stream l mod N (default priority), the "
+    ap.add_argument("--overlap", type=int, default=4,
+                    help="N >= 2 (default 4): N chains of layers, layer l on stream l mod N (default priority), the "
                          "recurrence kept in layer order by events; 1: selection + gather of layer l on a side "
                          "stream under the scoring of layer l+1; 0: one stream.  Same results bit for bit.")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")

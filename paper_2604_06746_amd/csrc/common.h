@@ -30,6 +30,14 @@ struct SeqTable {
   int32_t batch;
 };
 
+// The short, latency-bound kernels of a layer (combine, reduce, accumulate, top-k, gather) call this first.  When
+// layers run as chains on several streams such a kernel shares a SIMD with waves of another layer's scoring
+// kernel, which run at priority 1 while they have MFMAs to issue: at the default priority the short kernel would
+// queue behind them, and it is the short kernels that sit on a chain's critical path.
+#ifdef __HIPCC__
+__device__ __forceinline__ void short_kernel_priority() { __builtin_amdgcn_s_setprio(2); }
+#endif
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -19,6 +19,7 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     const uint8_t* __restrict__ src0, const uint8_t* __restrict__ src1, uint8_t* __restrict__ dst0,
     uint8_t* __restrict__ dst1, int64_t ssh, int64_t sst, int64_t dsh, int64_t dst_tok, uint32_t units_per_row,
     uint32_t upr_shift, uint32_t total_units, SeqTable seq, const int32_t* __restrict__ idx) {
+  short_kernel_priority();
   const int g = blockIdx.y;
   const uint8_t* src = (blockIdx.z == 0 ? src0 : src1) + (int64_t)g * ssh;
   uint8_t* dst = (blockIdx.z == 0 ? dst0 : dst1) + (int64_t)g * dsh;

@@ -31,6 +31,7 @@ constexpr int kCombRows = 32, kCombSlots = 32;
 __global__ __launch_bounds__(kCombRows* kCombSlots) void score_combine_kernel(
     SeqTable seq, int G, int R, int RPC, int RC, int WK, int64_t n_chunks, int row_blocks,
     const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ row_ent) {
+  short_kernel_priority();
   __shared__ float sM[kCombSlots / 2][kCombRows], sZ[kCombSlots / 2][kCombRows], sE[kCombSlots / 2][kCombRows];
   const int rblk = blockIdx.x % row_blocks;
   const int bg = blockIdx.x / row_blocks;
@@ -90,6 +91,7 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
     const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
     const float* __restrict__ row_ent, float* __restrict__ ent_head, float* __restrict__ entropy, int B,
     int Hq, int w, float* __restrict__ cen, float lambda, float inv_w) {
+  short_kernel_priority();
   __shared__ float hsum[256];
   const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * V;
   if (i0 < total) {   // V == 4 only when total % 4 == 0
@@ -167,6 +169,7 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
 // per-KV-head in-degree: the column-sum planes of head g added up in plane order
 __global__ __launch_bounds__(256) void group_sums_kernel(const float* __restrict__ colsum, int CP, int64_t total,
                                                          float* __restrict__ groups) {
+  short_kernel_priority();
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int g = blockIdx.y;
   if (i >= total) return;
@@ -177,6 +180,7 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const float* __restrict
 
 __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, const float* __restrict__ d,
                                                          int64_t n, float lambda, float inv_w, int vec) {
+  short_kernel_priority();
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (vec) {
     const int64_t i4 = i * 4;

@@ -410,12 +410,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       else issue_tile(s + PD, IntC<(decltype(slot_tag)::value + PD) % NBUF>{});
     }
   };
-  // one tile per step: row block 1's MFMAs run under row block 0's softmax
+  // one tile per step: row block 1's MFMAs run under row block 0's softmax.  While a wave still has MFMAs to
+  // issue it runs at a raised priority, and drops back for the trailing softmax, which is vector work only: the
+  // SIMD's other waves then get their MFMAs out ahead of it and the matrix pipe idles less (-3.5 % / -5 %).
   auto rest_of_tile = [&](auto masked_tag, int jbase, auto fixed_tag) __attribute__((always_inline)) {
     if constexpr (NRB == 2) {
+      __builtin_amdgcn_s_setprio(1);
       mfma_block(acc1, kf, IntC<NRB - 1>{});
       softmax_block(masked_tag, acc0, IntC<0>{}, jbase, fixed_tag);
       interleave_hint();
+      __builtin_amdgcn_s_setprio(0);
       softmax_block(masked_tag, acc1, IntC<NRB - 1>{}, jbase, fixed_tag);
     } else {
       softmax_block(masked_tag, acc0, IntC<0>{}, jbase, fixed_tag);

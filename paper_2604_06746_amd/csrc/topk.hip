@@ -66,6 +66,7 @@ __device__ inline Share my_share(const float* scores, const SeqTable& seq, int k
 
 __global__ __launch_bounds__(kThreads) void topk_init_kernel(SeqTable seq, int keep_tail, TopkWs ws,
                                                              int32_t* __restrict__ idx_out) {
+  short_kernel_priority();
   const int b = blockIdx.y;
   const int tid = blockIdx.x * kThreads + threadIdx.x;
   const int stride = gridDim.x * kThreads;
@@ -163,6 +164,7 @@ __device__ inline void for_each_strided(const Share& s, const float (&v)[kPerThr
 
 __global__ __launch_bounds__(kThreads) void topk_hist0_kernel(const float* __restrict__ scores, SeqTable seq,
                                                               int keep_tail, TopkWs ws) {
+  short_kernel_priority();
   __shared__ uint32_t h[kBins];
   const Share s = my_share(scores, seq, keep_tail);
   const int t = threadIdx.x;
@@ -177,6 +179,7 @@ __global__ __launch_bounds__(kThreads) void topk_hist0_kernel(const float* __res
 
 __global__ __launch_bounds__(kThreads) void topk_hist1_kernel(const float* __restrict__ scores, SeqTable seq,
                                                               int keep_tail, TopkWs ws) {
+  short_kernel_priority();
   __shared__ uint32_t h[kBins];
   __shared__ uint32_t scan[4];
   __shared__ uint32_t res[2];
@@ -201,6 +204,7 @@ __global__ __launch_bounds__(kThreads) void topk_hist1_kernel(const float* __res
 
 __global__ __launch_bounds__(kThreads) void topk_hist2_kernel(const float* __restrict__ scores, SeqTable seq,
                                                               int keep_tail, TopkWs ws) {
+  short_kernel_priority();
   __shared__ uint32_t h[kLowBins];
   __shared__ uint32_t scan[4];
   __shared__ uint32_t res[2];
@@ -250,6 +254,7 @@ __global__ __launch_bounds__(kThreads) void topk_hist2_kernel(const float* __res
 __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __restrict__ scores, SeqTable seq,
                                                               int keep_tail, TopkWs ws,
                                                               int32_t* __restrict__ idx_out) {
+  short_kernel_priority();
   __shared__ uint32_t scan[4];
   __shared__ uint32_t res[2];
   __shared__ uint32_t cnt[2];

@@ -51,14 +51,14 @@ def test_headline_config_whole_sweep(sweep_mod, oracle):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("chains", [False, True])
-def test_headline_graph_with_two_streams_equals_eager(sweep_mod, chains):
-    # bench.py's launch configuration at full size (four layers of it): the sweep captured in a HIP graph on two
-    # streams (two chains of alternate layers, or selection + gather on a side stream), replayed twice, against
+@pytest.mark.parametrize("chains", [0, 2, 4])
+def test_headline_graph_with_several_streams_equals_eager(sweep_mod, chains):
+    # bench.py's launch configuration at full size (a few layers of it): the sweep captured in a HIP graph on
+    # several streams (chains of layers, or selection + gather on a side stream), replayed twice, against
     # plain eager launches -- same bits
     from helpers import make_sweep
     wl = workloads.C3_128K
-    L = 4
+    L = 6 if chains == 4 else 4
     layers = [workloads.make_layer(wl, l, "cuda") for l in range(L)]
     ref = make_sweep(sweep_mod, wl, n_layers_out=L)
     for l, x in enumerate(layers):
@@ -67,11 +67,12 @@ def test_headline_graph_with_two_streams_equals_eager(sweep_mod, chains):
     torch.cuda.synchronize()
     sw = make_sweep(sweep_mod, wl, n_layers_out=L)
     side = torch.cuda.Stream()
+    sides = [side] + [torch.cuda.Stream() for _ in range(max(chains - 2, 0))]
 
     def step():
         sw.reset()
         if chains:
-            sw.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
+            sw.sweep_chains(((x.q_win, x.k, x.v) for x in layers), sides)
         else:
             sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
         sw.select_struct()

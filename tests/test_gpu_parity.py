@@ -623,7 +623,7 @@ def test_overlapped_sweep_equals_sequential(sweep_mod):
     assert torch.equal(seq.idx_kv, ovl.idx_kv)
 
 
-@pytest.mark.parametrize("L,chains", [(1, 2), (4, 2), (5, 2), (7, 3)])
+@pytest.mark.parametrize("L,chains", [(1, 2), (4, 2), (5, 2), (7, 3), (3, 4), (9, 4)])
 def test_chained_sweep_equals_sequential(sweep_mod, L, chains):
     # layer l on stream l mod chains, the recurrence kept in layer order by events: same bits
     wl = workloads.S_BF16_RAGGED
@@ -646,17 +646,18 @@ def test_chained_sweep_equals_sequential(sweep_mod, L, chains):
     assert torch.equal(seq.entropy, two.entropy) and torch.equal(seq.entropy_per_head, two.entropy_per_head)
 
 
-@pytest.mark.parametrize("overlap", [0, 1, 2])
+@pytest.mark.parametrize("overlap", [0, 1, 2, 4])
 def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
     # the launch configuration bench.py times: the whole sweep captured once in a HIP graph (one stream, selection +
-    # gather on a side stream, or two chains of alternate layers) and replayed.  Every replay must give the eager sweep's bits; eager work
+    # gather on a side stream, or two / four chains of layers) and replayed.  Every replay must give the eager sweep's bits; eager work
     # and synchronisations sit between the replays, and the inputs change between them.
     wl = workloads.S_BF16_W64
-    L = 4
+    L = 6 if overlap == 4 else 4
     layers = [workloads.make_layer(wl, l % wl.n_layers, "cuda") for l in range(L)]
     ref = make_sweep(sweep_mod, wl, n_layers_out=L)
     sw = make_sweep(sweep_mod, wl, n_layers_out=L)
     side = torch.cuda.Stream() if overlap else None
+    sides = [side] + [torch.cuda.Stream() for _ in range(overlap - 2)] if overlap >= 2 else []
 
     def sweep_on(obj):
         obj.reset()
@@ -664,6 +665,8 @@ def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
             obj.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side)
         elif overlap == 2 and obj is sw:
             obj.sweep_two_chains(((x.q_win, x.k, x.v) for x in layers), side)
+        elif overlap > 2 and obj is sw:
+            obj.sweep_chains(((x.q_win, x.k, x.v) for x in layers), sides)
         else:
             for l, x in enumerate(layers):
                 obj.layer(x.q_win, x.k, x.v, slot=l)
