@@ -6,9 +6,10 @@ for each layer  score_layer -> accumulate_centrality -> select_topk(D, k, keep w
 then one select_topk on the accumulated centrality.  Inputs (per-layer Q_win, K, V) are generated
 on the GPU before the timed region and stay resident in HBM; each layer has its own buffers.
 
-Prints ONE JSON line: scored KV tokens/s for the whole sweep, the HBM roofline of the dominant kernel
-(timed live with events in a separate profiled sweep of the same sequence), and the CPU oracle timed
-on a bounded sample of the same workload.
+Prints ONE JSON line: scored KV tokens/s for the whole sweep (median of the timed steps), the roofline of
+the dominant kernel against the three units it could be bound by (HBM, bf16 MFMA, vector-ALU issue slots),
+timed live with events in a separate profiled sweep of the same sequence, and the CPU oracle timed on a
+bounded sample of the same workload.
 """
 import argparse
 import json
@@ -40,7 +41,9 @@ def parse_args():
                          "recurrence kept in layer order by events; 1: selection + gather of layer l on a side "
                          "stream under the scoring of layer l+1; 0: one stream.  Same results bit for bit.")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
-    ap.add_argument("--cpu-sample-layers", type=int, default=32, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample-layers", type=int, default=-1,
+                    help="layers the CPU oracle is timed on (0 = skip; default: as many, spread evenly over the "
+                         "depth, as about 25 s of CPU work allow, at least 2)")
     return ap.parse_args()
 
 
@@ -104,13 +107,20 @@ def main():
 
     for _ in range(args.warmup):
         run()
+    # exactly `steps` steps between two synchronisations; an event between steps gives each step's own time
+    stream = torch.cuda.current_stream()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         run()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_mean = (t1 - t0) * 1e3 / args.steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_per_step = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     tokens_per_step = wl.total_tokens * L
     value = tokens_per_step / (ms_per_step * 1e-3)
 
@@ -118,7 +128,6 @@ def main():
     names = ["score_pass1", "score_combine", "score_pass2", "score_reduce", "accumulate", "select_topk", "gather_kv"]
     acc_ms = {k: 0.0 for k in names}
     n_meas = 0
-    stream = torch.cuda.current_stream()
     for rep in range(max(args.profile_steps, 0)):
         sw.reset()
         if rep == 0:
@@ -174,33 +183,50 @@ def main():
     extra = {}
     if n_meas:
         dom = "score_pass1" if kern_us["score_pass1"] >= kern_us["score_pass2"] else "score_pass2"
-        achieved = k_bytes / (kern_us[dom] * 1e-6) / 1e9
-        traffic = None
+        t_dom = kern_us[dom] * 1e-6
+        hbm_gbs = k_bytes / t_dom / 1e9
+        qk_flops = 2.0 * wl.n_q_heads * wl.window * wl.total_tokens * wl.head_dim      # Q_win K^T of one pass
+        mfma_tf = qk_flops / t_dom / 1e12
+        # wave-wide vector instruction slots the softmax of one pass needs at least (one lane per logit)
+        valu_slots = VALU_SLOTS_PER_LOGIT[dom] * wl.n_q_heads * wl.window * wl.total_tokens / 64.0
+        valu_gs = valu_slots / t_dom / 1e9
+        units = {
+            "hbm": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": k_bytes},
+            "mfma": {"achieved": round(mfma_tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(mfma_tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_launch": qk_flops},
+            "alu": {"achieved": round(valu_gs, 1), "peak": VALU_PEAK_GSLOTS, "unit": "G issue slots/s",
+                    "frac": round(valu_gs / VALU_PEAK_GSLOTS, 4), "slots_per_logit": VALU_SLOTS_PER_LOGIT[dom],
+                    "slots_per_launch": valu_slots},
+        }
+        # the unit that binds: the one the kernel uses the largest fraction of
+        binds = max(units, key=lambda u: units[u]["frac"])
+        traffic, traffic_source = None, None
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
             try:
-                traffic = json.load(open(tpath)).get(wl.name, {}).get(dom)
+                prof = json.load(open(tpath))
+                # counters of an earlier rocprofv3 --pmc run of pmc_workload.py, not of this run: only quoted
+                # while the library is the one that was profiled
+                if prof.get("_library_version") == B.structkv_version():
+                    traffic = prof.get(wl.name, {}).get(dom)
+                    traffic_source = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of pmc_workload.py; not measured in this run)"
             except Exception:
                 traffic = None
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                    "algorithmic_bytes_per_launch": k_bytes, "avg_launch_us": round(kern_us[dom], 2),
-                    "measured_copy_GBs": round(copy_gbs, 1), "frac_of_measured_copy": round(achieved / copy_gbs, 4)}
         score_us = sum(kern_us[k] for k in names[:4])
-        qk_flops = 2.0 * wl.n_q_heads * wl.window * wl.total_tokens * wl.head_dim      # Q_win K^T of one pass
-        # wave-wide vector instruction slots the softmax of one pass needs at least (one lane per logit)
-        valu_slots = VALU_SLOTS_PER_LOGIT[dom] * wl.n_q_heads * wl.window * wl.total_tokens / 64.0
+        roofline = {"bound": binds, "binds": binds, "kernel": dom, "achieved": units[binds]["achieved"],
+                    "peak": units[binds]["peak"], "unit": units[binds]["unit"], "frac": units[binds]["frac"],
+                    "traffic": traffic, "traffic_source": traffic_source, "avg_launch_us": round(kern_us[dom], 2),
+                    "hbm": units["hbm"], "mfma": units["mfma"], "alu": units["alu"],
+                    # the K stream with K counted ONCE per token per layer, over all four scoring kernels
+                    "k_once_all_scoring_kernels": {"achieved": round(k_bytes / (score_us * 1e-6) / 1e9, 1),
+                                                   "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                                   "frac": round(k_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+                    "measured_copy_GBs": round(copy_gbs, 1), "hbm_frac_of_measured_copy": round(hbm_gbs / copy_gbs, 4)}
         extra = {
-            "mfma": {"kernel": dom, "achieved_TFLOPs": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12, 1),
-                     "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
-                     "frac": round(qk_flops / (kern_us[dom] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "flops_per_launch": qk_flops},
-            "valu": {"kernel": dom, "slots_per_logit": VALU_SLOTS_PER_LOGIT[dom],
-                     "achieved_Gslots": round(valu_slots / (kern_us[dom] * 1e-6) / 1e9, 1), "peak_Gslots": VALU_PEAK_GSLOTS,
-                     "frac": round(valu_slots / (kern_us[dom] * 1e-6) / 1e9 / VALU_PEAK_GSLOTS, 4)},
             "kernel_us": {k: round(v, 2) for k, v in kern_us.items()},
-            "k_stream_both_passes": {"achieved_GBs": round(k_bytes / (score_us * 1e-6) / 1e9, 1),
-                                     "frac": round(k_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+            "kernel_us_note": "each kernel alone on one stream, eager, an event on either side; the timed steps "
+                              "run the layers as chains on several streams, where kernels share the chip",
             "gather": {"achieved_GBs": round(gather_bytes / (kern_us["gather_kv"] * 1e-6) / 1e9, 1),
                        "frac": round(gather_bytes / (kern_us["gather_kv"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                        "algorithmic_bytes_per_launch": gather_bytes},
@@ -208,10 +234,14 @@ def main():
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
-    if args.cpu_sample_layers > 0:
+    if args.cpu_sample_layers != 0:
         import oracle
         to_oracle_array = workloads.to_oracle_array
-        ns = min(args.cpu_sample_layers, L)
+        if args.cpu_sample_layers > 0:
+            ns = min(args.cpu_sample_layers, L)
+        else:   # ~25 s of oracle time: it scores about 3.6e5 tokens/s at a window of 64 on 16 threads
+            est_layer_s = wl.total_tokens * (wl.window / 64.0) / 3.6e5
+            ns = min(L, max(2, int(25.0 / max(est_layer_s, 1e-3))))
         sample = sorted(set(int(round(i * (L - 1) / max(ns - 1, 1))) for i in range(ns)))
         C = np.zeros(wl.total_tokens)
         cpu_s = 0.0
@@ -228,12 +258,15 @@ def main():
             cpu_s += time.perf_counter() - c0
         cpu = {"value": round(wl.total_tokens * len(sample) / cpu_s, 1), "unit": "scored KV tokens/s",
                "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "%d of %d layers (%s) of %s, all tokens; %.1f s" % (len(sample), L, sample, wl.name, cpu_s)}
+               "sample": "%d of %d layers (%s) of %s, all tokens; %.1f s%s" % (
+                   len(sample), L, sample, wl.name, cpu_s,
+                   "" if len(sample) == L else "; whole sweep extrapolated: %.0f s" % (cpu_s * L / len(sample)))}
 
     out = {
         "metric": "scored KV tokens/s per layer sweep (score+top-k+gather)",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_stat": "median of the timed steps (an event between steps)",
+        "ms_per_step_mean": round(ms_mean, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": L, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "seq_lens": list(wl.seq_lens) if wl.batch > 1 else wl.seq_lens[0],

@@ -2,12 +2,11 @@
  * libstructkv -- StructKV prefill scoring / selection / gather path for AMD MI355X (gfx950).
  *
  * C ABI.  Every tensor pointer is a DEVICE pointer unless marked "host".  The
- * library owns no memory and keeps no state between calls (the debug path
- * switch aside): the caller owns all
- * buffers, including the scratch `workspace` (size it with
- * structkv_workspace_bytes).  All work is enqueued on `stream` (a hipStream_t
- * passed as void*; NULL = the default stream); no call synchronises the
- * device.  Every entry point returns a structkv_status; on failure nothing has
+ * library owns no memory, reads no environment variable and keeps no state
+ * between calls: the caller owns all buffers, including the scratch
+ * `workspace` (size it with structkv_workspace_bytes).  All work is enqueued
+ * on `stream` (a hipStream_t passed as void*; NULL = the default stream); no
+ * call synchronises the device.  Every entry point returns a structkv_status; on failure nothing has
  * been enqueued unless the status is STRUCTKV_ERR_HIP, and
  * structkv_last_error() holds a thread-local message.  Inputs are assumed
  * finite (NaN/Inf behaviour is undefined).  Strides count ELEMENTS and are
@@ -228,34 +227,6 @@ structkv_status structkv_score_layer_pivot(const structkv_shape* shape, const vo
 structkv_status structkv_transition_scores(const double* entropy, const double* sparsity, const double* variance,
                                            int32_t n_layers, double w1, double w2, double w3, double* t_out,
                                            int32_t* pivot_layer_out);
-
-/*
- * Test hook: the attention rows themselves (paper Eq. 1) for ONE sequence of n tokens,
- * probs_out [H_q][w][n] fp32, computed by the same kernels as structkv_score_layer.
- * H_q*w*n must not exceed 2^26.
- */
-structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_win, const void* k,
-                                     int64_t k_stride_head, int64_t k_stride_tok, int64_t n,
-                                     float* probs_out, void* workspace, size_t workspace_bytes,
-                                     void* stream);
-
-/*
- * Profiling hook: structkv_score_layer with only some of its four kernels enqueued, so a caller can
- * bracket each with events.  step_mask bits: 1 = pass 1 (row statistics), 2 = combine (lse, entropy
- * per head), 4 = pass 2 (column sums), 8 = reduce (in-degree, entropy).  Steps read what earlier steps
- * left in the workspace; mask 15 is structkv_score_layer itself.
- */
-structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,
-                                           int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
-                                           const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
-                                           float* entropy_per_head_out, void* workspace,
-                                           size_t workspace_bytes, void* stream, int32_t step_mask);
-
-/*
- * Test hook: force the scoring path.  0 = automatic (bf16 MFMA kernels when the shape and alignment
- * allow, SIMT kernels otherwise), 1 = always SIMT.  Process-wide; returns the previous value.
- */
-int32_t structkv_debug_force_path(int32_t path);
 
 #ifdef __cplusplus
 }

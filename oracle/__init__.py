@@ -16,15 +16,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "structkv_oracle.c")
-_LIB = os.path.join(_HERE, "libstructkv_oracle.so")
+# STRUCTKV_ORACLE_SANITIZE=1 (set by tests/test_host_sanitizers.py for its child process) selects a build with
+# AddressSanitizer and UndefinedBehaviorSanitizer; the process must then have libasan preloaded.
+_SANITIZE = os.environ.get("STRUCTKV_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "libstructkv_oracle_san.so" if _SANITIZE else "libstructkv_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (x86-64-v3 so the binary also runs on the GPU machine's host)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC", "-std=c11",
-               "-o", _LIB, _SRC, "-lm"]
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"] if _SANITIZE else ["-O3"]
+        cmd = ["gcc"] + opt + ["-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC", "-std=c11",
+                               "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

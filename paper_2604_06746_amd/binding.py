@@ -29,7 +29,7 @@ EXPORTS = (
     "structkv_select_topk",
     "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
     "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_score_layer_pivot", "structkv_transition_scores",
-    "structkv_debug_probs", "structkv_debug_force_path", "structkv_debug_score_steps",
+    "structkv_debug_probs", "structkv_debug_score_steps",
 )
 
 
@@ -60,7 +60,7 @@ _lib.structkv_workspace_bytes.argtypes = [_sp, _i32, _i64]
 _lib.structkv_score_layer.restype = _i32
 _lib.structkv_score_layer.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.structkv_debug_score_steps.restype = _i32
-_lib.structkv_debug_score_steps.argtypes = _lib.structkv_score_layer.argtypes + [_i32]
+_lib.structkv_debug_score_steps.argtypes = _lib.structkv_score_layer.argtypes + [_i32, _i32]
 _lib.structkv_accumulate_centrality.restype = _i32
 _lib.structkv_accumulate_centrality.argtypes = [_vp, _vp, _i64, _f32, _f32, _vp]
 _lib.structkv_score_layer_accumulate.restype = _i32
@@ -89,9 +89,7 @@ _lib.structkv_transition_scores.restype = _i32
 _lib.structkv_transition_scores.argtypes = [_vp, _vp, _vp, _i32, ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                             _vp, _vp]
 _lib.structkv_debug_probs.restype = _i32
-_lib.structkv_debug_probs.argtypes = [_sp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
-_lib.structkv_debug_force_path.restype = _i32
-_lib.structkv_debug_force_path.argtypes = [_i32]
+_lib.structkv_debug_probs.argtypes = [_sp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp, _i32]
 
 
 def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, window: int, dtype: int,
@@ -126,10 +124,6 @@ def structkv_version() -> int:
     return int(_lib.structkv_version())
 
 
-def structkv_debug_force_path(path: int) -> int:
-    return int(_lib.structkv_debug_force_path(path))
-
-
 def structkv_workspace_bytes(shape: Optional[structkv_shape], batch: int, total_tokens: int) -> int:
     return int(_lib.structkv_workspace_bytes(ctypes.byref(shape) if shape is not None else None, batch,
                                              total_tokens))
@@ -151,13 +145,13 @@ def structkv_score_layer(shape: structkv_shape, q_win: torch.Tensor, k: torch.Te
 def structkv_debug_score_steps(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor,
                                cu_seqlens: Sequence[int], indeg_out: torch.Tensor, entropy_out: torch.Tensor,
                                entropy_per_head_out: Optional[torch.Tensor], workspace: torch.Tensor,
-                               step_mask: int, stream=None) -> None:
+                               step_mask: int, stream=None, force_simt: bool = False) -> None:
     cu = _host_i64(cu_seqlens)
     _check(_lib.structkv_debug_score_steps(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1),
                                            len(cu_seqlens) - 1, cu, _ptr(indeg_out), _ptr(entropy_out),
                                            _ptr(entropy_per_head_out), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream(stream),
-                                           step_mask))
+                                           step_mask, int(bool(force_simt))))
 
 
 def structkv_accumulate_centrality(centrality: torch.Tensor, indeg: torch.Tensor, lam: float, inv_w: float,
@@ -284,7 +278,9 @@ def structkv_transition_scores(entropy: Sequence[float], sparsity: Sequence[floa
 
 
 def structkv_debug_probs(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, n: int,
-                         probs_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+                         probs_out: torch.Tensor, workspace: torch.Tensor, stream=None,
+                         force_simt: bool = False) -> None:
     _check(_lib.structkv_debug_probs(ctypes.byref(shape), _ptr(q_win), _ptr(k), k.stride(0), k.stride(1), n,
                                      _ptr(probs_out), _ptr(workspace),
-                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+                                     workspace.numel() * workspace.element_size(), _stream(stream),
+                                     int(bool(force_simt))))

@@ -1,8 +1,8 @@
 // C-ABI entry points of libstructkv: argument validation, work planning, workspace carving and
 // kernel launches.  No device memory is allocated here; nothing synchronises the device.
 #include "common.h"
+#include "../../include/structkv_debug.h"
 
-#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -12,7 +12,6 @@
 namespace skv {
 
 static thread_local char g_err[512] = "";
-static std::atomic<int> g_force_path{0};
 
 structkv_status fail(structkv_status st, const char* fmt, ...) {
   va_list ap;
@@ -60,18 +59,6 @@ structkv_status check_cu(int32_t batch, const int64_t* cu, SeqTable* seq) {
   return STRUCTKV_OK;
 }
 
-// Tuning knobs for kernel experiments, read from the environment once per process:
-// STRUCTKV_DEBUG_RB (32-row blocks per wave: 1, 2), STRUCTKV_DEBUG_NW (waves per workgroup: 1, 2, 4),
-// STRUCTKV_DEBUG_KC (keys per workgroup: a multiple of 32, at least 256).  Unset or invalid: the plan's own choice.
-struct TuningKnobs { long rb, nw, kc; };
-const TuningKnobs& tuning_knobs() {
-  static const TuningKnobs k = [] {
-    auto get = [](const char* name) { const char* e = getenv(name); return e ? atol(e) : 0L; };
-    return TuningKnobs{get("STRUCTKV_DEBUG_RB"), get("STRUCTKV_DEBUG_NW"), get("STRUCTKV_DEBUG_KC")};
-  }();
-  return k;
-}
-
 // Decide path, tiling and workspace layout.  `n_chunk_bound` < 0: exact from seq; otherwise an upper bound.
 void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t total, bool mfma_ok,
                ScorePlan* p) {
@@ -86,12 +73,9 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     // rows.  Waves of 64 rows beat waves of 128 rows (256 registers, two per SIMD) by 6 % at 256 rows and by
     // 20-25 % at 128 rows: more waves hide more of the MFMA -> softmax latency.
     p->RB = p->R > 32 ? 2 : 1;
-    const TuningKnobs& knobs = tuning_knobs();
-    if (knobs.rb == 1 || knobs.rb == 2) p->RB = (int)knobs.rb;
     p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
     p->NW = p->RC > 2 ? 4 : (p->RC > 1 ? 2 : 1);
-    if (knobs.nw == 1 || knobs.nw == 2 || knobs.nw == 4) p->NW = (int)knobs.nw;
     // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave, 4 two-wave
     // or 8 one-wave workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
     // (RPC*d*2 bytes per wave) stays small against the K stream
@@ -103,7 +87,6 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     int64_t kc = ceil_div(ceil_div(total, chunks_per_round * rounds), 32) * 32;
     if (kc < 256) kc = 256;
     if (kc > kMaxKC) kc = kMaxKC;
-    if (knobs.kc >= 256 && knobs.kc % 32 == 0 && knobs.kc <= kMaxKC) kc = knobs.kc;
     p->KC = (int)kc;
     p->CP = (int)ceil_div(p->RC, p->NW);
   } else {
@@ -129,7 +112,6 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
 }
 
 bool mfma_eligible(const structkv_shape& s, const void* q, const void* k, int64_t ksh, int64_t kst) {
-  if (g_force_path.load() == 1) return false;
   if (s.dtype != STRUCTKV_DTYPE_BF16) return false;
   if (s.head_dim != 64 && s.head_dim != 128) return false;
   if (s.causal && (s.window % 32) != 0) return false;   // the MFMA kernels' causal masks assume whole 32-row blocks per head
@@ -138,18 +120,27 @@ bool mfma_eligible(const structkv_shape& s, const void* q, const void* k, int64_
   return true;
 }
 
+// What a scoring call does beyond structkv_score_layer itself.
+struct ScoreOpts {
+  int step_mask = 15;          // which of the four kernels are enqueued (profiling hook)
+  float* centrality = nullptr; // the reduce kernel also applies C <- lambda C + inv_w D
+  float lambda = 0.f, inv_w = 0.f;
+  float* groups = nullptr;     // per-KV-head in-degree [G][total]
+  int kshare = 1;              // consecutive groups that read one K head (per-head scoring)
+  bool force_simt = false;     // test hook: SIMT kernels even where the MFMA kernels apply
+  float* probs = nullptr;      // test hook: the attention rows themselves
+};
+
 structkv_status run_score(const structkv_shape* shape, const void* q_win, const void* k, int64_t ksh,
                           int64_t kst, const SeqTable& seq_in, float* indeg, float* entropy,
-                          float* ent_head_out, float* probs, void* ws, size_t ws_bytes, hipStream_t st,
-                          int step_mask = 15, float* centrality = nullptr, float lambda = 0.f,
-                          float inv_w = 0.f, float* groups = nullptr, int kshare = 1) {
+                          float* ent_head_out, void* ws, size_t ws_bytes, hipStream_t st, const ScoreOpts& o) {
   const structkv_shape& s = *shape;
   SeqTable seq = seq_in;
   const int B = seq.batch;
   const int64_t total = seq.cu[B];
   ScorePlan p;
-  make_plan(s, &seq, B, total, mfma_eligible(s, q_win, k, ksh, kst), &p);
-  p.kshare = kshare;   // s.n_kv_heads % kshare == 0 (the caller's business)
+  make_plan(s, &seq, B, total, !o.force_simt && mfma_eligible(s, q_win, k, ksh, kst), &p);
+  p.kshare = o.kshare;   // s.n_kv_heads % kshare == 0 (the caller's business)
   if (p.total_bytes > ws_bytes)
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, p.total_bytes);
   if ((int64_t)s.n_kv_heads * p.RC * p.n_chunks >= ((int64_t)1 << 31))
@@ -169,15 +160,15 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   const float scale = s.scale > 0.f ? s.scale : 1.0f / std::sqrt((float)s.head_dim);
   const float c2 = (float)((double)scale * 1.4426950408889634);
   auto pass = p.path == 0 ? launch_score_mfma_ring : launch_score_simt;
-  if (step_mask & 1)
+  if (o.step_mask & 1)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, nullptr, 1, st));
-  if (step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, st));
-  if (step_mask & 4)
-    SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, probs, 2, st));
-  if (step_mask & 8)
-    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, centrality,
-                                      lambda, inv_w, st));
-  if (groups) SKV_HIP_CHECK(launch_group_sums(s, p, colsum, total, groups, st));
+  if (o.step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, st));
+  if (o.step_mask & 4)
+    SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, o.probs, 2, st));
+  if (o.step_mask & 8)
+    SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, o.centrality,
+                                      o.lambda, o.inv_w, st));
+  if (o.groups) SKV_HIP_CHECK(launch_group_sums(s, p, colsum, total, o.groups, st));
   return STRUCTKV_OK;
 }
 
@@ -191,8 +182,6 @@ extern "C" {
 const char* structkv_last_error(void) { return g_err; }
 
 int32_t structkv_version(void) { return 100; }
-
-int32_t structkv_debug_force_path(int32_t path) { return g_force_path.exchange(path == 1 ? 1 : 0); }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;
@@ -212,9 +201,7 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
                                         int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
                                         const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                         float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
-                                        void* stream, int step_mask, float* centrality = nullptr,
-                                        float lambda = 0.f, float inv_w = 0.f, float* groups = nullptr,
-                                        int kshare = 1) {
+                                        void* stream, const ScoreOpts& opts = ScoreOpts()) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -237,8 +224,7 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
   if (!workspace || ((uintptr_t)workspace & 255))
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg_out, entropy_out,
-                   entropy_per_head_out, nullptr, workspace, workspace_bytes, (hipStream_t)stream, step_mask,
-                   centrality, lambda, inv_w, groups, kshare);
+                   entropy_per_head_out, workspace, workspace_bytes, (hipStream_t)stream, opts);
 }
 
 structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_win, const void* k,
@@ -247,7 +233,7 @@ structkv_status structkv_score_layer(const structkv_shape* shape, const void* q_
                                      float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
                                      void* stream) {
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
-                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15);
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream);
 }
 
 structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, const void* q_win, const void* k,
@@ -263,9 +249,10 @@ structkv_status structkv_score_layer_accumulate(const structkv_shape* shape, con
     return fail(STRUCTKV_ERR_INVALID_ARG, "centrality is NULL or not 4-byte aligned");
   if (centrality && centrality == indeg_out)
     return fail(STRUCTKV_ERR_INVALID_ARG, "centrality must not alias indeg_out");
+  ScoreOpts o;
+  o.centrality = centrality; o.lambda = lambda; o.inv_w = inv_w;
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
-                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15, centrality,
-                          lambda, inv_w);
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, o);
 }
 
 structkv_status structkv_score_layer_groups(const structkv_shape* shape, const void* q_win, const void* k,
@@ -276,24 +263,29 @@ structkv_status structkv_score_layer_groups(const structkv_shape* shape, const v
   clear_error();
   if (batch != 0 && (!indeg_groups_out || ((uintptr_t)indeg_groups_out & 3)))
     return fail(STRUCTKV_ERR_INVALID_ARG, "indeg_groups_out is NULL or not 4-byte aligned");
+  ScoreOpts o;
+  o.groups = indeg_groups_out;
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
-                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, 15, nullptr, 0.f,
-                          0.f, indeg_groups_out);
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, o);
 }
 
 structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,
                                            int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
                                            const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                            float* entropy_per_head_out, void* workspace,
-                                           size_t workspace_bytes, void* stream, int32_t step_mask) {
+                                           size_t workspace_bytes, void* stream, int32_t step_mask,
+                                           int32_t force_simt) {
+  ScoreOpts o;
+  o.step_mask = step_mask & 15;
+  o.force_simt = force_simt != 0;
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
-                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, step_mask & 15);
+                          entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, o);
 }
 
 structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_win, const void* k,
                                      int64_t k_stride_head, int64_t k_stride_tok, int64_t n,
                                      float* probs_out, void* workspace, size_t workspace_bytes,
-                                     void* stream) {
+                                     void* stream, int32_t force_simt) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -315,8 +307,11 @@ structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_
   if (st != STRUCTKV_OK) return st;
   float* indeg = (float*)((uint8_t*)workspace + base);
   float* ent = (float*)((uint8_t*)workspace + base + align_up(sizeof(float) * (size_t)n, 256));
-  return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg, ent, nullptr, probs_out,
-                   workspace, base, (hipStream_t)stream);
+  ScoreOpts o;
+  o.probs = probs_out;
+  o.force_simt = force_simt != 0;
+  return run_score(shape, q_win, k, k_stride_head, k_stride_tok, seq, indeg, ent, nullptr, workspace, base,
+                   (hipStream_t)stream, o);
 }
 
 structkv_status structkv_accumulate_centrality(float* centrality, const float* indeg, int64_t total_tokens,
@@ -564,10 +559,12 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
       const int64_t cu1[2] = {0, n};
       const uint8_t* qs = (const uint8_t*)q_win + (size_t)b * Hq * w * d * e;
       const uint8_t* ks = (const uint8_t*)k + (size_t)seq.cu[b] * k_stride_tok * e;
+      ScoreOpts o;
+      o.groups = heads; o.kshare = gs;
       st = score_layer_impl(&sub, qs, ks, k_stride_head, k_stride_tok, 1, cu1,
                             indeg_out ? indeg_out + seq.cu[b] : indeg, entropy_out ? entropy_out + b : ent,
                             entropy_head_out ? entropy_head_out + (size_t)b * Hq : ent_h, w8 + c.off_score_ws,
-                            c.score_ws_bytes, stream, 15, nullptr, 0.f, 0.f, heads, gs);
+                            c.score_ws_bytes, stream, o);
       if (st != STRUCTKV_OK) return st;
       // the ceil(top_frac n) largest keys of every head: heads are the "sequences" of one selection call
       int64_t kk = (int64_t)std::ceil(top_frac * (double)n);

@@ -36,6 +36,17 @@ struct SeqTable {
 // queue behind them, and it is the short kernels that sit on a chain's critical path.
 #ifdef __HIPCC__
 __device__ __forceinline__ void short_kernel_priority() { __builtin_amdgcn_s_setprio(2); }
+
+// merge partial softmax statistics (M, Z, E) of two disjoint key sets, log2 domain:
+//   Z = sum 2^(x-M),  E = sum 2^(x-M) (x-M)
+__device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float Z2, float E2) {
+  const float Mn = fmaxf(M, M2);
+  const float d1 = M - Mn, d2 = M2 - Mn;
+  const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
+  E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
+  Z = Z * f1 + Z2 * f2;
+  M = Mn;
+}
 #endif
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -9,10 +9,7 @@ namespace skv {
 namespace {
 
 constexpr int kThreads = 256;
-#ifndef SKV_GATHER_UNROLL
-#define SKV_GATHER_UNROLL 1
-#endif
-constexpr int kUnroll = SKV_GATHER_UNROLL;
+constexpr int kUnroll = 1;   // units per thread
 
 template <typename V, bool POW2>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(

@@ -13,16 +13,6 @@ namespace {
 
 constexpr float kLn2 = 0.6931471805599453f;
 
-// merge (M, Z, E) of two disjoint key sets, log2 domain: Z = sum 2^(x-M), E = sum 2^(x-M)(x-M)
-__device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float Z2, float E2) {
-  const float Mn = fmaxf(M, M2);
-  const float d1 = M - Mn, d2 = M2 - Mn;
-  const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
-  E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
-  Z = Z * f1 + Z2 * f2;
-  M = Mn;
-}
-
 // one workgroup of 1024 threads per (sequence b, KV head g, block of 32 query rows): thread = (row,
 // slot); the 32 slots of a row split its partial statistics (consecutive threads read consecutive rows,
 // the contiguous direction of the partials), then merge in a fixed order: lane pairs, then waves

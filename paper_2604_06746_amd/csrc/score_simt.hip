@@ -18,17 +18,6 @@ __device__ inline float ld_elem(const __hip_bfloat16* p, int64_t i) {
   return __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(p)[i]) << 16);
 }
 
-// merge partial softmax statistics (M, Z, E) of two disjoint key sets, log2 domain:
-//   Z = sum 2^(x-M),  E = sum 2^(x-M) (x-M)
-__device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float Z2, float E2) {
-  const float Mn = fmaxf(M, M2);
-  const float d1 = M - Mn, d2 = M2 - Mn;
-  const float f1 = __builtin_amdgcn_exp2f(d1), f2 = __builtin_amdgcn_exp2f(d2);
-  E = (E + d1 * Z) * f1 + (E2 + d2 * Z2) * f2;
-  Z = Z * f1 + Z2 * f2;
-  M = Mn;
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void score_simt_kernel(
     const T* __restrict__ q, const T* __restrict__ k, int64_t ksh, int64_t kst, int kshare, SeqTable seq,

@@ -2,13 +2,13 @@
 plus one plain copy of known size (the gather kernel with identity indices: reads and writes
 exactly copy_bytes each), which calibrates the FETCH_SIZE / WRITE_SIZE scale.
 
-    rocprofv3 --pmc FETCH_SIZE -d out -- python3 -m paper_2604_06746_amd.pmc_workload --layers 2
+    rocprofv3 --pmc FETCH_SIZE -d out -- python3 pmc_workload.py --layers 2
 """
 import argparse
 import os
 import sys
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main():

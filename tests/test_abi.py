@@ -22,9 +22,12 @@ def B():
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "structkv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(structkv_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("structkv.h", "structkv_debug.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(structkv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_symbols_are_exported(B):
@@ -223,3 +226,43 @@ def test_entry_points_exist():
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     assert callable(mod.build) and callable(mod.smoke)
+
+
+def test_host_planning_with_stub_launchers(B):
+    """Valid calls all the way through work planning and workspace carving.  Only in the host-only sanitizer
+    build (tests/test_host_sanitizers.py), whose kernel launchers are stubs: no pointer is dereferenced."""
+    lib = B._lib
+    if not hasattr(lib, "structkv_stub_launch_count"):
+        pytest.skip("the real library launches kernels; this runs against the stub build only")
+    i64 = ctypes.c_int64
+    fake, fake2 = ctypes.c_void_p(1 << 20), ctypes.c_void_p(1 << 21)
+    rng = np.random.default_rng(3)
+    before = lib.structkv_stub_launch_count()
+    for (Hq, G, d, w, dtype, causal) in [(32, 8, 128, 64, 1, 0), (32, 8, 128, 32, 1, 1), (8, 8, 64, 32, 0, 0),
+                                         (4, 1, 64, 8, 1, 0), (6, 2, 96, 5, 1, 0), (32, 32, 128, 64, 1, 0),
+                                         (16, 2, 128, 64, 1, 0)]:
+        shape = B.make_shape(Hq, G, d, w, dtype, bool(causal))
+        for batch in (1, 3, B.STRUCTKV_MAX_BATCH):
+            lens = [int(x) for x in rng.integers(w, 5000, size=batch)]
+            if batch == 3:
+                lens[1] = 0                                  # an empty sequence in the middle
+            cu = (i64 * (batch + 1))(*np.concatenate([[0], np.cumsum(lens)]).tolist())
+            total = int(sum(lens))
+            need = B.structkv_workspace_bytes(shape, batch, total)
+            assert need > 0 and need % 256 == 0
+            args = (ctypes.byref(shape), fake, fake, total * d, d, batch, cu, fake, fake, None, fake2)
+            assert lib.structkv_score_layer(*args, need, None) == B.STRUCTKV_OK, B.structkv_last_error()
+            assert lib.structkv_score_layer(*args, need - 256, None) in (B.STRUCTKV_OK, B.STRUCTKV_ERR_WORKSPACE)
+            assert lib.structkv_score_layer(*args, 256, None) == B.STRUCTKV_ERR_WORKSPACE
+            ks = (i64 * batch)(*[max(n - w, 0) // 3 for n in lens])
+            assert lib.structkv_select_topk(fake, batch, cu, ks, w if min(x for x in lens if x) >= w and 0 not in lens else 0,
+                                            fake, fake2, need, None) == B.STRUCTKV_OK, B.structkv_last_error()
+            rows = (i64 * batch)(*[int(k) for k in ks])
+            assert lib.structkv_gather_kv(fake, fake, total * d, d, fake2, fake2, sum(rows) * d, d, G, d, 2, batch, cu,
+                                          rows, fake, None) == B.STRUCTKV_OK, B.structkv_last_error()
+            assert lib.structkv_block_scores(fake, batch, cu, 16, fake2, None) == B.STRUCTKV_OK
+        pneed = B.structkv_pivot_workspace_bytes(shape, 4096)
+        cu1 = (i64 * 3)(0, 4096, 4096 + 100 + w)
+        assert lib.structkv_score_layer_pivot(ctypes.byref(shape), fake, fake, 5000 * d, d, 2, cu1, 0.1, fake, fake, None,
+                                              fake, fake, fake2, pneed, None) == B.STRUCTKV_OK, B.structkv_last_error()
+    assert lib.structkv_stub_launch_count() > before

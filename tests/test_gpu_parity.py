@@ -49,12 +49,8 @@ def test_attention_rows_match_oracle(B, oracle, name, causal, force_simt):
     shape = B.make_shape(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, code, causal)
     ws = torch.empty(B.structkv_workspace_bytes(shape, 1, n) + 4 * n + 1024, dtype=torch.uint8, device="cuda")
     probs = torch.full((wl.n_q_heads, wl.window, n), -1.0, dtype=torch.float32, device="cuda")
-    prev = B.structkv_debug_force_path(1 if force_simt else 0)
-    try:
-        B.structkv_debug_probs(shape, x.q_win, x.k, n, probs, ws)
-        torch.cuda.synchronize()
-    finally:
-        B.structkv_debug_force_path(prev)
+    B.structkv_debug_probs(shape, x.q_win, x.k, n, probs, ws, force_simt=force_simt)
+    torch.cuda.synchronize()
     _, _, _, p_ref = oracle.score_layer(to_oracle_array(x.q_win), to_oracle_array(x.k), wl.n_q_heads,
                                         wl.n_kv_heads, wl.head_dim, wl.window, [n], causal=causal,
                                         want_probs=True)
@@ -79,24 +75,24 @@ def test_score_layer_matches_oracle(B, sweep_mod, oracle, name, causal, force_si
     if causal and min(wl.seq_lens) < wl.window:
         pytest.skip("causal needs n >= w")
     sw = make_sweep(sweep_mod, wl, causal)
-    prev = B.structkv_debug_force_path(1 if force_simt else 0)
-    try:
-        for layer in range(min(wl.n_layers, 2)):
-            x = workloads.make_layer(wl, layer, "cuda")
-            sw.indeg.fill_(-7.0)
+    for layer in range(min(wl.n_layers, 2)):
+        x = workloads.make_layer(wl, layer, "cuda")
+        sw.indeg.fill_(-7.0)
+        if force_simt:       # all four kernels of the scoring call, SIMT variants
+            B.structkv_debug_score_steps(sw.shape, x.q_win, x.k, sw.cu, sw.indeg, sw.entropy, sw.entropy_per_head,
+                                         sw.workspace, 15, force_simt=True)
+        else:
             sw.score(x.q_win, x.k)
-            torch.cuda.synchronize()
-            D, ent, ent_h, _ = oracle_layer(oracle, wl, x, causal)
-            got = sw.indeg.cpu().numpy()
-            assert_close_floor(got, D, _tol(wl), "indeg layer %d" % layer)
-            off = 0
-            for n in wl.seq_lens:                       # in-degree total per sequence is w * H_q
-                assert abs(got[off:off + n].astype(np.float64).sum() - wl.window * wl.n_q_heads) < 1e-4 * wl.window * wl.n_q_heads
-                off += n
-            assert_entropy(sw.entropy.cpu().numpy()[:wl.batch], ent, _tol(wl))
-            assert_entropy(sw.entropy_per_head.cpu().numpy()[:wl.batch], ent_h, _tol(wl))
-    finally:
-        B.structkv_debug_force_path(prev)
+        torch.cuda.synchronize()
+        D, ent, ent_h, _ = oracle_layer(oracle, wl, x, causal)
+        got = sw.indeg.cpu().numpy()
+        assert_close_floor(got, D, _tol(wl), "indeg layer %d" % layer)
+        off = 0
+        for n in wl.seq_lens:                       # in-degree total per sequence is w * H_q
+            assert abs(got[off:off + n].astype(np.float64).sum() - wl.window * wl.n_q_heads) < 1e-4 * wl.window * wl.n_q_heads
+            off += n
+        assert_entropy(sw.entropy.cpu().numpy()[:wl.batch], ent, _tol(wl))
+        assert_entropy(sw.entropy_per_head.cpu().numpy()[:wl.batch], ent_h, _tol(wl))
 
 
 @pytest.mark.parametrize("name", ["s_bf16_w64", "s_bf16_gqa4", "s_bf16_r192", "s_f32_ragged"])
