@@ -4,7 +4,8 @@
  * C ABI.  Every tensor pointer is a DEVICE pointer unless marked "host".  The
  * library owns no memory, reads no environment variable and keeps no state
  * between calls: the caller owns all buffers, including the scratch
- * `workspace` (size it with structkv_workspace_bytes).  All work is enqueued
+ * `workspace` (size it with structkv_workspace_bytes); the one exception is
+ * structkv_select_topk_static, whose scratch is an array inside the library.  All work is enqueued
  * on `stream` (a hipStream_t passed as void*; NULL = the default stream); no
  * call synchronises the device.  Every entry point returns a structkv_status; on failure nothing has
  * been enqueued unless the status is STRUCTKV_ERR_HIP, and
@@ -136,6 +137,23 @@ structkv_status structkv_score_layer_groups(const structkv_shape* shape, const v
 structkv_status structkv_select_topk(const float* scores, int32_t batch, const int64_t* cu_seqlens,
                                      const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * structkv_select_topk for callers that cannot allocate or hold a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same result
+ * bit for bit.  Its scratch (digit histograms, search state, per-workgroup suffix sums) is a fixed 4 MiB
+ * array inside the library, one copy per GPU, held until the process ends; the call allocates nothing.
+ * Limit: the scratch covers any batch of up to STRUCTKV_MAX_BATCH sequences with at most
+ * STRUCTKV_STATIC_TOPK_MAX_TOKENS tokens in all (a single sequence may be about twice that long); a larger
+ * call returns STRUCTKV_ERR_UNSUPPORTED with nothing enqueued.  All calls on one GPU share the array: calls
+ * that overlap in time on the same GPU (different streams, different threads) race; serialise them, or use
+ * structkv_select_topk with separate workspaces.  Nothing needs clearing between calls (every call starts
+ * by zeroing the histograms it uses, on the stream).
+ */
+#define STRUCTKV_STATIC_TOPK_MAX_TOKENS 1048576
+structkv_status structkv_select_topk_static(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                            const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
+                                            void* stream);
 
 /*
  * Decoupled cache store (paper Alg. 1 line 17): compact the selected K and V rows.

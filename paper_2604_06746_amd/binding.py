@@ -22,11 +22,12 @@ STRUCTKV_ERR_HIP = 4
 STRUCTKV_DTYPE_F32 = 0
 STRUCTKV_DTYPE_BF16 = 1
 STRUCTKV_MAX_BATCH = 64
+STRUCTKV_STATIC_TOPK_MAX_TOKENS = 1048576
 
 EXPORTS = (
     "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
     "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_score_layer_groups",
-    "structkv_select_topk",
+    "structkv_select_topk", "structkv_select_topk_static",
     "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
     "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_score_layer_pivot", "structkv_transition_scores",
     "structkv_debug_probs", "structkv_debug_score_steps",
@@ -70,6 +71,8 @@ _lib.structkv_score_layer_groups.restype = _i32
 _lib.structkv_score_layer_groups.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.structkv_select_topk.restype = _i32
 _lib.structkv_select_topk.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+_lib.structkv_select_topk_static.restype = _i32
+_lib.structkv_select_topk_static.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp]
 _lib.structkv_gather_kv.restype = _i32
 _lib.structkv_gather_kv.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp,
                                     _vp, _vp, _vp]
@@ -195,6 +198,13 @@ def structkv_select_topk(scores: torch.Tensor, cu_seqlens: Sequence[int], k_per_
     _check(_lib.structkv_select_topk(_ptr(scores), len(k_per_seq), cu, ks, keep_tail, _ptr(idx_out),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
                                      _stream(stream)))
+
+
+def structkv_select_topk_static(scores: torch.Tensor, cu_seqlens: Sequence[int], k_per_seq: Sequence[int],
+                                keep_tail: int, idx_out: torch.Tensor, stream=None) -> None:
+    cu, ks = _host_i64(cu_seqlens), _host_i64(k_per_seq)
+    _check(_lib.structkv_select_topk_static(_ptr(scores), len(k_per_seq), cu, ks, keep_tail, _ptr(idx_out),
+                                            _stream(stream)))
 
 
 def structkv_gather_kv(k_src: Optional[torch.Tensor], v_src: Optional[torch.Tensor],

@@ -330,37 +330,70 @@ structkv_status structkv_accumulate_centrality(float* centrality, const float* i
   return STRUCTKV_OK;
 }
 
-structkv_status structkv_select_topk(const float* scores, int32_t batch, const int64_t* cu_seqlens,
-                                     const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
-  clear_error();
-  SeqTable seq;
-  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+// shared by the two selection entry points: validates, fills seq.k / seq.out_off; *rows_out = output entries
+static structkv_status check_topk_args(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                       const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out, SeqTable* seq,
+                                       int64_t* rows_out) {
+  *rows_out = 0;
+  structkv_status st = check_cu(batch, cu_seqlens, seq);
   if (st != STRUCTKV_OK) return st;
   if (batch == 0) return STRUCTKV_OK;
   if (!k_per_seq) return fail(STRUCTKV_ERR_INVALID_ARG, "k_per_seq is NULL");
   if (keep_tail < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "keep_tail < 0");
   int64_t out = 0;
   for (int b = 0; b < batch; ++b) {
-    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    const int64_t n = seq->cu[b + 1] - seq->cu[b];
     if (keep_tail > n)
       return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: keep_tail (%d) > n (%lld)", b, keep_tail, (long long)n);
     if (k_per_seq[b] < 0 || k_per_seq[b] > n - keep_tail)
       return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d: k (%lld) outside [0, n - keep_tail = %lld]", b,
                   (long long)k_per_seq[b], (long long)(n - keep_tail));
-    seq.k[b] = (int32_t)k_per_seq[b];
-    seq.out_off[b] = out;
+    seq->k[b] = (int32_t)k_per_seq[b];
+    seq->out_off[b] = out;
     out += k_per_seq[b] + keep_tail;
   }
-  seq.out_off[batch] = out;
+  seq->out_off[batch] = out;
   if (out == 0) return STRUCTKV_OK;
   if (!scores || !idx_out) return fail(STRUCTKV_ERR_INVALID_ARG, "scores or idx_out is NULL");
+  *rows_out = out;
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_select_topk(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                     const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  SeqTable seq;
+  int64_t rows = 0;
+  structkv_status st = check_topk_args(scores, batch, cu_seqlens, k_per_seq, keep_tail, idx_out, &seq, &rows);
+  if (st != STRUCTKV_OK || rows == 0) return st;
   if (!workspace || ((uintptr_t)workspace & 255))
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   const size_t need = topk_workspace_bytes(batch, seq.cu[batch]);
   if (workspace_bytes < need)
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, top-k needs %zu", workspace_bytes, need);
   SKV_HIP_CHECK(launch_topk(scores, seq, keep_tail, idx_out, workspace, (hipStream_t)stream));
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_select_topk_static(const float* scores, int32_t batch, const int64_t* cu_seqlens,
+                                            const int64_t* k_per_seq, int32_t keep_tail, int32_t* idx_out,
+                                            void* stream) {
+  clear_error();
+  SeqTable seq;
+  int64_t rows = 0;
+  structkv_status st = check_topk_args(scores, batch, cu_seqlens, k_per_seq, keep_tail, idx_out, &seq, &rows);
+  if (st != STRUCTKV_OK || rows == 0) return st;
+  void* scratch_ptr = nullptr;
+  size_t scratch_bytes = 0;
+  SKV_HIP_CHECK(topk_static_scratch(&scratch_ptr, &scratch_bytes));
+  const size_t need = topk_workspace_bytes(batch, seq.cu[batch]);
+  if (need > scratch_bytes)
+    return fail(STRUCTKV_ERR_UNSUPPORTED,
+                "this selection needs %zu bytes of scratch, the library's static scratch holds %zu "
+                "(enough for %d sequences with %d tokens in all); use structkv_select_topk with a workspace",
+                need, scratch_bytes, kMaxBatch, STRUCTKV_STATIC_TOPK_MAX_TOKENS);
+  SKV_HIP_CHECK(launch_topk(scores, seq, keep_tail, idx_out, scratch_ptr, (hipStream_t)stream));
   return STRUCTKV_OK;
 }
 

@@ -91,6 +91,8 @@ hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, 
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);
 size_t topk_workspace_bytes(int batch, int64_t total_tokens);
+// the library's own top-k scratch on the current device (structkv_select_topk_static); no allocation
+hipError_t topk_static_scratch(void** ptr, size_t* bytes);
 // pivot metrics: partial sums part [H][kPivotMaxSlices][2] of every head, then the means over the heads
 constexpr int kPivotMaxSlices = 64;
 hipError_t launch_pivot_heads(const float* heads, int H, int64_t n, const int32_t* idx, int64_t k, float inv_w,

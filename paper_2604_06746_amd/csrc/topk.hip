@@ -16,8 +16,17 @@
 // Ties at the threshold go to the lowest indices; no floating-point atomics anywhere.
 #include "common.h"
 
+#include <mutex>
+
 namespace skv {
 namespace {
+
+// Scratch of structkv_select_topk_static, the entry point for callers that cannot allocate: the histograms,
+// search state and per-workgroup suffix sums that structkv_select_topk takes from the caller's workspace live
+// here instead.  Every GPU the library runs on holds its own copy until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kThreads = 256;
 constexpr int kBins = 2048;               // digits 0 and 1: 11 bits
@@ -361,6 +370,28 @@ size_t topk_workspace_bytes(int batch, int64_t total_tokens) {
   const size_t nb = max_blocks(batch, total_tokens);
   return align_up(sizeof(uint32_t) * 3 * B * kBins, 256) + align_up(sizeof(uint32_t) * 4 * B, 256) +
          align_up(sizeof(uint32_t) * kLowBins * nb, 256) + align_up(sizeof(uint32_t) * 2 * nb, 256);
+}
+
+// Device address and size of the static scratch on the CURRENT device (looked up once per device).
+hipError_t topk_static_scratch(void** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* dev_ptr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (dev_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr || ((uintptr_t)p & 255)) return hipErrorInvalidSymbol;
+    dev_ptr[dev] = p;
+  }
+  *ptr = dev_ptr[dev];
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
 }
 
 // seq.out_off must hold the output offsets, seq.k the budgets.

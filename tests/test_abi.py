@@ -125,6 +125,14 @@ def test_invalid_arguments_are_rejected_on_the_host(B):
     assert topk(fake, 1, cu, (i64 * 1)(10), 0, None, fake, ws_bytes, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert topk(fake, 1, cu, (i64 * 1)(0), 0, fake, fake, ws_bytes, None) == B.STRUCTKV_OK   # nothing to do
 
+    stat = lib.structkv_select_topk_static          # same validation; fails before it looks for its scratch
+    assert stat(fake, 1, cu, (i64 * 1)(101), 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert stat(fake, 1, cu, (i64 * 1)(10), -1, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert stat(fake, 1, cu, None, 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert stat(None, 1, cu, (i64 * 1)(10), 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert stat(fake, 1, cu, (i64 * 1)(0), 0, fake, None) == B.STRUCTKV_OK   # nothing to do
+    assert stat(None, 0, cu, None, 0, None, None) == B.STRUCTKV_OK
+
     blk = lib.structkv_block_scores
     assert blk(fake, 1, cu, 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert blk(None, 1, cu, 16, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
