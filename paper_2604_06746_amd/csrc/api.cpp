@@ -648,6 +648,20 @@ structkv_status structkv_score_layer_pivot(const structkv_shape* shape, const vo
                     stream);
 }
 
+// Eq. 7: t[l] += weight * (g_l - min g) / (max g - min g) for l >= 1, with g_l = direction * (m[l] - m[l-1]);
+// a metric whose steps are all equal has no transition to point at and adds nothing.
+static void add_normalised_gradient(const double* m, int n_layers, double direction, double weight, double* t) {
+  double g_min = 0.0, g_max = 0.0;
+  for (int l = 1; l < n_layers; ++l) {
+    const double g = direction * (m[l] - m[l - 1]);
+    if (l == 1 || g < g_min) g_min = g;
+    if (l == 1 || g > g_max) g_max = g;
+  }
+  const double span = g_max - g_min;
+  if (!(span > 0.0)) return;
+  for (int l = 1; l < n_layers; ++l) t[l] += weight * ((direction * (m[l] - m[l - 1]) - g_min) / span);
+}
+
 structkv_status structkv_transition_scores(const double* entropy, const double* sparsity, const double* variance,
                                            int32_t n_layers, double w1, double w2, double w3, double* t_out,
                                            int32_t* pivot_layer_out) {
@@ -658,25 +672,15 @@ structkv_status structkv_transition_scores(const double* entropy, const double* 
   if (!pivot_layer_out) return fail(STRUCTKV_ERR_INVALID_ARG, "pivot_layer_out is NULL");
   for (int l = 0; l < n_layers; ++l) t_out[l] = 0.0;
   if (n_layers < 2) { *pivot_layer_out = n_layers; return STRUCTKV_OK; }
-  const double* metric[3] = {entropy, sparsity, variance};
-  const double sign[3] = {-1.0, 1.0, 1.0};   // a DROP in entropy, a RISE in sparsity and variance
-  const double weight[3] = {w1, w2, w3};
-  for (int m = 0; m < 3; ++m) {
-    // first differences, then min-max scaling over the layers that have one
-    double lo = sign[m] * (metric[m][1] - metric[m][0]), hi = lo;
-    for (int l = 2; l < n_layers; ++l) {
-      const double dl = sign[m] * (metric[m][l] - metric[m][l - 1]);
-      lo = dl < lo ? dl : lo;
-      hi = dl > hi ? dl : hi;
-    }
-    if (!(hi > lo)) continue;
-    for (int l = 1; l < n_layers; ++l)
-      t_out[l] += weight[m] * (sign[m] * (metric[m][l] - metric[m][l - 1]) - lo) / (hi - lo);
-  }
-  int best = 1;
-  for (int l = 2; l < n_layers; ++l)
-    if (t_out[l] > t_out[best]) best = l;
-  *pivot_layer_out = best + 1;
+  // Eq. 8: the detector looks for a DROP in entropy together with a RISE in sparsity and in variance
+  add_normalised_gradient(entropy, n_layers, -1.0, w1, t_out);
+  add_normalised_gradient(sparsity, n_layers, +1.0, w2, t_out);
+  add_normalised_gradient(variance, n_layers, +1.0, w3, t_out);
+  // Eq. 9: the first layer after the strongest transition (the lowest such layer on ties)
+  int32_t at = 1;
+  for (int32_t l = 2; l < n_layers; ++l)
+    if (t_out[l] > t_out[at]) at = l;
+  *pivot_layer_out = at + 1;
   return STRUCTKV_OK;
 }
 

@@ -9,7 +9,7 @@ to_oracle_array = workloads.to_oracle_array   # torch fp32 / bf16 tensor -> the 
 
 
 def _tol(wl):
-    return 2e-5 if wl.dtype == "f32" else 1e-3
+    return 1e-5 if wl.dtype == "f32" else 1e-3
 
 
 def assert_close_floor(got, ref, rel, what):
@@ -88,12 +88,19 @@ def sweep_against_oracle(sweep_mod, oracle, wl, layers, check_dormant=False):
             hubs = workloads.hub_positions(wl)
             act = workloads.hub_active(wl, layer)
             ro = 0
+            n_dormant = dormant_kept = 0
             for b in range(wl.batch):
                 sel = set(got_idx[ro:ro + sw.rows_per_seq[b]].tolist())
                 for p, a in zip(hubs[b], act[b]):
                     if a:
                         assert p in sel, "active hub %d missed at layer %d" % (p, layer)
+                    else:
+                        n_dormant += 1
+                        dormant_kept += p in sel
                 ro += sw.rows_per_seq[b]
+            # a hub that is dormant at this layer is an ordinary key here: a single-layer snapshot keeps it only
+            # by chance (the budget is 3-6 % of the tokens)
+            assert dormant_kept <= 0.25 * max(n_dormant, 1) + 2, (layer, dormant_kept, n_dormant)
     assert abs(total_mass - w * wl.n_q_heads * wl.batch * len(layers)) < 1e-4 * w * wl.n_q_heads * wl.batch * len(layers)
     return sw, C
 

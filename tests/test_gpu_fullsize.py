@@ -1,10 +1,11 @@
 """GPU parity at the BASELINE sizes, in the launch configuration bench.py times.
 
-One layer of each full-size configuration is generated on the GPU (the same generator bench.py uses),
-run through the HIP path and compared with the CPU oracle on the same bits: in-degree and entropy
-element by element (the oracle finishes a 128K-token layer in seconds on the host cores), the top-k
-bit-for-bit on the GPU's own scores, the gather byte-for-byte; the million-token configuration is checked
-the same way on one layer.
+Layers of each full-size configuration are generated on the GPU (the same generator bench.py uses), run
+through the HIP path and compared with the CPU oracle on the same bits: in-degree, entropy and the centrality
+accumulated over the sampled layers element by element (the oracle finishes a 128K-token layer in seconds on
+the host cores), the top-k bit-for-bit on the GPU's own scores, the gather byte-for-byte.  Four layers of the
+32K configuration, four layers of the ragged batch, an early and a late layer of the million-token sequence (each
+holds active and dormant hubs), every layer of the headline 128K configuration.
 """
 import numpy as np
 import pytest
@@ -22,11 +23,17 @@ def sweep_mod():
     return sweep
 
 
-@pytest.mark.parametrize("name,layers", [("c2_llama8b_32k", (0, 17)), ("c3_llama8b_128k", (5,)),
-                                         ("c5_ragged_batch8", (3,))])
+@pytest.mark.parametrize("name,layers", [("c2_llama8b_32k", (0, 9, 17, 30)), ("c3_llama8b_128k", (5,)),
+                                         ("c5_ragged_batch8", (3, 12, 20, 28))])
 def test_full_size_layers(sweep_mod, oracle, name, layers):
     wl = workloads.WORKLOADS[name]
-    sweep_against_oracle(sweep_mod, oracle, wl, layers, check_dormant=True)
+    sw, C = sweep_against_oracle(sweep_mod, oracle, wl, layers, check_dormant=True)
+    # the structural selection on the centrality accumulated over these layers (Eq. 10), on the GPU's own scores
+    sw.select_struct()
+    torch.cuda.synchronize()
+    got = sw.idx_struct.cpu().numpy()[:sw.rows]
+    c_gpu = sw.centrality.cpu().numpy()
+    assert np.array_equal(got, np.concatenate(oracle.select_topk(c_gpu, wl.seq_lens, wl.k_per_seq, wl.window)))
     torch.cuda.empty_cache()
 
 
@@ -119,9 +126,13 @@ def test_pivot_metrics_at_32k(sweep_mod, oracle):
     torch.cuda.empty_cache()
 
 
-def test_million_token_layer(sweep_mod, oracle):
+def test_million_token_layers(sweep_mod, oracle):
+    # an early and a late layer, both with active and with dormant hubs among the 1024 planted ones
     wl = workloads.C4_1M
-    sweep_against_oracle(sweep_mod, oracle, wl, (9,), check_dormant=True)
+    for layer in (2, 29):
+        act = workloads.hub_active(wl, layer)[0]
+        assert any(act) and not all(act)
+    sweep_against_oracle(sweep_mod, oracle, wl, (2, 29), check_dormant=True)
     torch.cuda.empty_cache()
 
 

@@ -91,6 +91,40 @@ def test_brute_force_tiny_python_loops(oracle):
     assert ent[0] == pytest.approx(sum(eh) / Hq, rel=1e-13)
 
 
+def test_brute_force_causal_python_loops(oracle):
+    # the causal reading (window row i, at position n-w+i, sees keys j <= n-w+i) in pure Python on random data,
+    # GQA, w > 1, n not a multiple of anything; catches an off-by-one in the visible range, a mask applied per
+    # head instead of per window row, masked keys that still receive mass
+    Hq, G, d, w, n = 6, 3, 4, 3, 7
+    q, k = _rand((1, Hq, w, d), 15), _rand((G, n, d), 16)
+    D, ent, ent_h, p = _score(oracle, q, k, Hq, G, d, w, n, causal=True, want_probs=True)
+    gs = Hq // G
+    Dref = [0.0] * n
+    eh = []
+    for h in range(Hq):
+        g = h // gs
+        acc_e = 0.0
+        for i in range(w):
+            vis = n - w + i + 1                       # keys 0 .. n-w+i
+            s = [sum(float(q[0, h, i, c]) * float(k[g, j, c]) for c in range(d)) / math.sqrt(d) for j in range(vis)]
+            m = max(s)
+            e = [math.exp(x - m) for x in s]
+            Z = sum(e)
+            a = [x / Z for x in e]
+            for j in range(vis):
+                Dref[j] += a[j]
+            assert p[0][h, i, :vis] == pytest.approx(a, rel=1e-13)
+            assert np.all(p[0][h, i, vis:] == 0.0)
+            acc_e += -sum(x * math.log(x) for x in a)
+        eh.append(acc_e / w)
+    assert D == pytest.approx(Dref, rel=1e-13)
+    assert ent_h[0] == pytest.approx(eh, rel=1e-13)
+    assert ent[0] == pytest.approx(sum(eh) / Hq, rel=1e-13)
+    assert sum(Dref) == pytest.approx(w * Hq, rel=1e-13)      # every visible row still sums to 1
+    # the last key is seen by the last window row only: its in-degree is at most H_q
+    assert D[n - 1] <= Hq
+
+
 def test_explicit_scale_and_default(oracle):
     Hq, G, d, w, n = 2, 1, 16, 4, 50
     q, k = _rand((1, Hq, w, d), 7), _rand((G, n, d), 8)
@@ -396,6 +430,20 @@ def test_transition_scores_hand_values(oracle):
     # weights only scale their own term
     T, _ = oracle.transition_scores(H, rho, V, (1.0, 0.0, 0.0))
     assert T.tolist() == pytest.approx([0.0, 0.0, 0.0, 1.0, 0.0])
+    # a second case worked by hand, other weights, entropy that also rises, variance that mostly FALLS:
+    #   -dH : -.5  1   .5  -.25  -> (x + .5)/1.5     = 0    1   2/3  1/6
+    #   drho: -.125 .5 -.125 .5  -> (x + .125)/.625  = 0    1   0    1
+    #   dV  : -2   1  -4   -1    -> (x + 4)/5        = 2/5  1   0    3/5
+    #   T = .5 a + .25 b + .25 c = .1, 1, 1/3, 1/12 + 1/4 + 3/20;  argmax at l = 2 -> L* = 3
+    # catches: a sign flipped on one metric, min-max taken over the raw metric instead of its differences,
+    # weights applied to the wrong metric, L* off by one
+    T, ls = oracle.transition_scores([4.0, 4.5, 3.5, 3.0, 3.25], [0.25, 0.125, 0.625, 0.5, 1.0],
+                                     [8.0, 6.0, 7.0, 3.0, 2.0], (0.5, 0.25, 0.25))
+    assert T.tolist() == pytest.approx([0.0, 0.1, 1.0, 1.0 / 3, 1.0 / 12 + 0.25 + 0.15], rel=1e-14)
+    assert ls == 3
+    # equal maxima: the lowest layer wins
+    T, ls = oracle.transition_scores([2.0, 1.0, 1.0, 0.0], [0.5] * 4, [1.0] * 4, (1.0, 0.0, 0.0))
+    assert T.tolist() == [0.0, 1.0, 0.0, 1.0] and ls == 2
 
 
 def test_golden_rational_sweep(oracle):
