@@ -40,6 +40,8 @@ def parse_args():
                     help="N >= 2 (default 4): N chains of layers, layer l on stream l mod N (default priority), the "
                          "recurrence kept in layer order by events; 1: selection + gather of layer l on a side "
                          "stream under the scoring of layer l+1; 0: one stream.  Same results bit for bit.")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="chains call the four entry points one by one instead of the fused structkv_layer_step")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
     ap.add_argument("--cpu-sample-layers", type=int, default=-1,
                     help="layers the CPU oracle is timed on (0 = skip; default: as many, spread evenly over the "
@@ -76,7 +78,7 @@ def main():
     def step():
         sw.reset()
         if args.overlap >= 2:
-            sw.sweep_chains(((x.q_win, x.k, x.v) for x in layers), side_streams)
+            sw.sweep_chains(((x.q_win, x.k, x.v) for x in layers), side_streams, fused=not args.separate_calls)
         elif side_stream is not None:
             sw.sweep_overlapped(((x.q_win, x.k, x.v) for x in layers), side_stream)
         else:

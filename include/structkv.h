@@ -172,6 +172,55 @@ structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t
                                    const int32_t* idx, void* stream);
 
 /*
+ * One layer of the hot path in one call (paper Alg. 1 lines 4, 6, 16, 17; Eq. 1-4, Eq. 13):
+ *   structkv_score_layer            -> indeg_out, entropy_out, entropy_per_head_out
+ *   structkv_accumulate_centrality  -> centrality (skipped when centrality == NULL: a caller that runs layers
+ *                                      on several streams applies the recurrence itself, in layer order)
+ *   structkv_select_topk(indeg_out, k_per_seq, keep_tail) -> idx_out
+ *   structkv_gather_kv(k, v, idx_out) -> k_dst, v_dst   (rows_b = k_b + keep_tail; either dst may be NULL)
+ * with the results of those four calls bit for bit, in eight kernel launches instead of eleven: the kernel
+ * that forms the in-degree also applies the recurrence, histograms the first radix digit of the selection and
+ * writes the kept window's indices (the scoring kernel before it has cleared the histograms).
+ * v shares k's strides (kv_stride_head, kv_stride_tok) and element type; k_dst / v_dst share
+ * dst_stride_head / dst_stride_tok.  Other arguments as in the four calls.
+ * workspace: structkv_layer_step_workspace_bytes(shape, batch, total_tokens) bytes (scoring and selection
+ * scratch are live together), 256-byte aligned, no initialisation needed.
+ */
+size_t structkv_layer_step_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens);
+structkv_status structkv_layer_step(const structkv_shape* shape, const void* q_win, const void* k, const void* v,
+                                    int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                    const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                    float* indeg_out, float* centrality, float lambda, float inv_w,
+                                    float* entropy_out, float* entropy_per_head_out, int32_t* idx_out,
+                                    void* k_dst, void* v_dst, int64_t dst_stride_head, int64_t dst_stride_tok,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * structkv_layer_step in two halves, for callers that run the layers of a prefill on several streams and must
+ * apply the centrality recurrence (paper Eq. 3 / Alg. 1 line 6) in layer order BETWEEN the halves:
+ *   structkv_layer_begin  : the scoring (Eq. 1, 2, 4) -> indeg_out, entropies; the first radix digit of the
+ *                           selection and the kept window's indices; with centrality != NULL also the
+ *                           recurrence (then this is the first four kernels of structkv_layer_step)
+ *   (the caller: wait for the previous layer's update, structkv_accumulate_centrality, signal)
+ *   structkv_layer_finish : the rest of the selection (Eq. 13) -> idx_out, and the selected rows -> k_dst, v_dst
+ * Both take the same arguments as structkv_layer_step (finish only those it uses), on the same stream, with the
+ * same workspace, whose contents must survive from begin to finish; indeg must not change in between.
+ */
+structkv_status structkv_layer_begin(const structkv_shape* shape, const void* q_win, const void* k, const void* v,
+                                     int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                     const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                     float* indeg_out, float* centrality, float lambda, float inv_w,
+                                     float* entropy_out, float* entropy_per_head_out, int32_t* idx_out,
+                                     void* k_dst, void* v_dst, int64_t dst_stride_head, int64_t dst_stride_tok,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+structkv_status structkv_layer_finish(const structkv_shape* shape, const void* k, const void* v,
+                                      int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                      const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                      const float* indeg, int32_t* idx_out, void* k_dst, void* v_dst,
+                                      int64_t dst_stride_head, int64_t dst_stride_tok, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
+/*
  * Structural truncation (paper Eq. 11-12): keep the hidden states and the position ids of the
  * structural indices, in index order.
  *   h_dst[o_b + i][:]  = h_src[cu[b] + idx[o_b + i]][:]          (hidden_dim*elem_bytes bytes, bit-exact)

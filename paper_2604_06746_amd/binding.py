@@ -28,7 +28,9 @@ EXPORTS = (
     "structkv_last_error", "structkv_version", "structkv_workspace_bytes", "structkv_score_layer",
     "structkv_accumulate_centrality", "structkv_score_layer_accumulate", "structkv_score_layer_groups",
     "structkv_select_topk", "structkv_select_topk_static",
-    "structkv_gather_kv", "structkv_truncate_hidden", "structkv_block_scores",
+    "structkv_gather_kv", "structkv_layer_step", "structkv_layer_step_workspace_bytes", "structkv_layer_begin",
+    "structkv_layer_finish",
+    "structkv_truncate_hidden", "structkv_block_scores",
     "structkv_pivot_workspace_bytes", "structkv_pivot_metrics", "structkv_score_layer_pivot", "structkv_transition_scores",
     "structkv_debug_probs", "structkv_debug_score_steps",
 )
@@ -76,6 +78,16 @@ _lib.structkv_select_topk_static.argtypes = [_vp, _i32, _vp, _vp, _i32, _vp, _vp
 _lib.structkv_gather_kv.restype = _i32
 _lib.structkv_gather_kv.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp,
                                     _vp, _vp, _vp]
+_lib.structkv_layer_step_workspace_bytes.restype = _sz
+_lib.structkv_layer_step_workspace_bytes.argtypes = [_sp, _i32, _i64]
+_lib.structkv_layer_step.restype = _i32
+_lib.structkv_layer_step.argtypes = [_sp, _vp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _f32, _vp,
+                                     _vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]
+_lib.structkv_layer_begin.restype = _i32
+_lib.structkv_layer_begin.argtypes = _lib.structkv_layer_step.argtypes
+_lib.structkv_layer_finish.restype = _i32
+_lib.structkv_layer_finish.argtypes = [_sp, _vp, _vp, _i64, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64,
+                                       _vp, _sz, _vp]
 _lib.structkv_truncate_hidden.restype = _i32
 _lib.structkv_truncate_hidden.argtypes = [_vp, _i64, _vp, _i64, _i32, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp]
 _lib.structkv_block_scores.restype = _i32
@@ -221,6 +233,51 @@ def structkv_gather_kv(k_src: Optional[torch.Tensor], v_src: Optional[torch.Tens
                                    _ptr(v_dst), dst.stride(0), dst.stride(1), src.shape[0], src.shape[2],
                                    src.element_size(), len(rows_per_seq), cu, rows, _ptr(idx),
                                    _stream(stream)))
+
+
+def structkv_layer_step_workspace_bytes(shape: structkv_shape, batch: int, total_tokens: int) -> int:
+    return int(_lib.structkv_layer_step_workspace_bytes(ctypes.byref(shape), batch, total_tokens))
+
+
+def structkv_layer_step(shape: structkv_shape, q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor],
+                        cu_seqlens: Sequence[int], k_per_seq: Sequence[int], keep_tail: int,
+                        indeg_out: torch.Tensor, centrality: Optional[torch.Tensor], lam: float, inv_w: float,
+                        entropy_out: torch.Tensor, entropy_per_head_out: Optional[torch.Tensor],
+                        idx_out: torch.Tensor, k_dst: Optional[torch.Tensor], v_dst: Optional[torch.Tensor],
+                        workspace: torch.Tensor, stream=None, _entry=None) -> None:
+    """k, v: [G, total, d] views sharing strides; k_dst, v_dst: [G, rows, d] views sharing strides (or None)."""
+    fn = _entry or _lib.structkv_layer_step
+    assert k.dim() == 3 and k.stride(2) == 1 and q_win.is_contiguous()
+    if v is not None:
+        assert v.stride() == k.stride() and v.dtype == k.dtype
+    dst = k_dst if k_dst is not None else v_dst
+    if k_dst is not None and v_dst is not None:
+        assert k_dst.stride() == v_dst.stride()
+    cu, ks = _host_i64(cu_seqlens), _host_i64(k_per_seq)
+    _check(fn(ctypes.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), k.stride(0), k.stride(1),
+              len(k_per_seq), cu, ks, keep_tail, _ptr(indeg_out), _ptr(centrality), lam, inv_w,
+              _ptr(entropy_out), _ptr(entropy_per_head_out), _ptr(idx_out), _ptr(k_dst),
+              _ptr(v_dst), dst.stride(0) if dst is not None else 0,
+              dst.stride(1) if dst is not None else 0, _ptr(workspace),
+              workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def structkv_layer_begin(*args, **kwargs) -> None:
+    """Same arguments as structkv_layer_step; enqueues its first half."""
+    structkv_layer_step(*args, _entry=_lib.structkv_layer_begin, **kwargs)
+
+
+def structkv_layer_finish(shape: structkv_shape, k: torch.Tensor, v: Optional[torch.Tensor],
+                          cu_seqlens: Sequence[int], k_per_seq: Sequence[int], keep_tail: int, indeg: torch.Tensor,
+                          idx_out: torch.Tensor, k_dst: Optional[torch.Tensor], v_dst: Optional[torch.Tensor],
+                          workspace: torch.Tensor, stream=None) -> None:
+    dst = k_dst if k_dst is not None else v_dst
+    cu, ks = _host_i64(cu_seqlens), _host_i64(k_per_seq)
+    _check(_lib.structkv_layer_finish(ctypes.byref(shape), _ptr(k), _ptr(v), k.stride(0), k.stride(1), len(k_per_seq),
+                                      cu, ks, keep_tail, _ptr(indeg), _ptr(idx_out), _ptr(k_dst), _ptr(v_dst),
+                                      dst.stride(0) if dst is not None else 0,
+                                      dst.stride(1) if dst is not None else 0, _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def structkv_truncate_hidden(h_src: Optional[torch.Tensor], h_dst: Optional[torch.Tensor],

@@ -85,7 +85,11 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     const int64_t chunks_per_round = slots / wg_per_chunk > 0 ? slots / wg_per_chunk : 1;
     const int64_t rounds = ceil_div(total > 0 ? total : 1, chunks_per_round * kMaxKC);
     int64_t kc = ceil_div(ceil_div(total, chunks_per_round * rounds), 32) * 32;
-    if (kc < 256) kc = 256;
+    // Short inputs: at least 512 keys per workgroup while that still fills half of the resident slots (a
+    // workgroup's fixed costs -- query operands, the first tiles' latency, the partial results -- weigh as much
+    // as 6-8 tiles; with layers running as chains the other half of the chip is another layer's), else 256.
+    const int64_t kc_min = ceil_div(total, 512) * wg_per_chunk * 2 >= slots ? 512 : 256;
+    if (kc < kc_min) kc = kc_min;
     if (kc > kMaxKC) kc = kMaxKC;
     p->KC = (int)kc;
     p->CP = (int)ceil_div(p->RC, p->NW);
@@ -129,6 +133,7 @@ struct ScoreOpts {
   int kshare = 1;              // consecutive groups that read one K head (per-head scoring)
   bool force_simt = false;     // test hook: SIMT kernels even where the MFMA kernels apply
   float* probs = nullptr;      // test hook: the attention rows themselves
+  const SelectFusion* fuse = nullptr;   // fused layer step: the small kernels also start the selection
 };
 
 structkv_status run_score(const structkv_shape* shape, const void* q_win, const void* k, int64_t ksh,
@@ -162,12 +167,14 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   auto pass = p.path == 0 ? launch_score_mfma_ring : launch_score_simt;
   if (o.step_mask & 1)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, nullptr, 1, st));
-  if (o.step_mask & 2) SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, st));
+  if (o.step_mask & 2)
+    SKV_HIP_CHECK(launch_score_combine(s, p, seq, stats, lse2, row_ent, o.fuse ? o.fuse->hist : nullptr,
+                                       o.fuse ? (int64_t)3 * kTopkBins * B : 0, st));
   if (o.step_mask & 4)
     SKV_HIP_CHECK(pass(s, p, seq, q_win, k, ksh, kst, c2, stats, lse2, colsum, total, o.probs, 2, st));
   if (o.step_mask & 8)
     SKV_HIP_CHECK(launch_score_reduce(s, p, seq, colsum, total, indeg, row_ent, ent_head, entropy, o.centrality,
-                                      o.lambda, o.inv_w, st));
+                                      o.lambda, o.inv_w, o.fuse, st));
   if (o.groups) SKV_HIP_CHECK(launch_group_sums(s, p, colsum, total, o.groups, st));
   return STRUCTKV_OK;
 }
@@ -201,7 +208,8 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
                                         int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,
                                         const int64_t* cu_seqlens, float* indeg_out, float* entropy_out,
                                         float* entropy_per_head_out, void* workspace, size_t workspace_bytes,
-                                        void* stream, const ScoreOpts& opts = ScoreOpts()) {
+                                        void* stream, const ScoreOpts& opts = ScoreOpts(),
+                                        const SeqTable* selection = nullptr) {
   clear_error();
   structkv_status st = check_shape(shape);
   if (st != STRUCTKV_OK) return st;
@@ -209,6 +217,10 @@ static structkv_status score_layer_impl(const structkv_shape* shape, const void*
   st = check_cu(batch, cu_seqlens, &seq);
   if (st != STRUCTKV_OK) return st;
   if (batch == 0) return STRUCTKV_OK;
+  if (selection) {   // a fused layer step: budgets and output offsets of the selection travel with the table
+    for (int b = 0; b < batch; ++b) { seq.k[b] = selection->k[b]; seq.out_off[b] = selection->out_off[b]; }
+    seq.out_off[batch] = selection->out_off[batch];
+  }
   const int64_t total = seq.cu[batch];
   if (!q_win || !entropy_out) return fail(STRUCTKV_ERR_INVALID_ARG, "q_win or entropy_out is NULL");
   if (total > 0 && (!k || !indeg_out)) return fail(STRUCTKV_ERR_INVALID_ARG, "k or indeg_out is NULL");
@@ -397,14 +409,15 @@ structkv_status structkv_select_topk_static(const float* scores, int32_t batch, 
   return STRUCTKV_OK;
 }
 
-structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t src_stride_head,
-                                   int64_t src_stride_tok, void* k_dst, void* v_dst, int64_t dst_stride_head,
-                                   int64_t dst_stride_tok, int32_t n_kv_heads, int32_t head_dim,
-                                   int32_t elem_bytes, int32_t batch, const int64_t* cu_seqlens,
-                                   const int64_t* rows_per_seq, const int32_t* idx, void* stream) {
-  clear_error();
-  SeqTable seq;
-  structkv_status st = check_cu(batch, cu_seqlens, &seq);
+// shared by structkv_gather_kv and structkv_layer_step: validates, fills seq->out_off from rows_per_seq
+static structkv_status check_gather_args(const void* k_src, const void* v_src, int64_t src_stride_head,
+                                         int64_t src_stride_tok, void* k_dst, void* v_dst, int64_t dst_stride_head,
+                                         int64_t dst_stride_tok, int32_t n_kv_heads, int32_t head_dim,
+                                         int32_t elem_bytes, int32_t batch, const int64_t* cu_seqlens,
+                                         const int64_t* rows_per_seq, const int32_t* idx, bool idx_needed,
+                                         SeqTable* seq, bool* nothing_to_do) {
+  *nothing_to_do = true;
+  structkv_status st = check_cu(batch, cu_seqlens, seq);
   if (st != STRUCTKV_OK) return st;
   if (n_kv_heads < 1 || head_dim < 1) return fail(STRUCTKV_ERR_INVALID_ARG, "n_kv_heads and head_dim must be >= 1");
   if (n_kv_heads > 65535) return fail(STRUCTKV_ERR_UNSUPPORTED, "n_kv_heads > 65535");
@@ -416,29 +429,181 @@ structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t
   if (src_stride_head < 0 || dst_stride_head < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "negative head stride");
   int64_t out = 0;
   for (int b = 0; b < batch; ++b) {
-    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    const int64_t n = seq->cu[b + 1] - seq->cu[b];
     if (rows_per_seq[b] < 0) return fail(STRUCTKV_ERR_INVALID_ARG, "rows_per_seq[%d] < 0", b);
     if (rows_per_seq[b] > 0 && n == 0)
       return fail(STRUCTKV_ERR_INVALID_ARG, "sequence %d is empty but rows_per_seq is %lld", b,
                   (long long)rows_per_seq[b]);
-    seq.out_off[b] = out;
+    seq->out_off[b] = out;
     out += rows_per_seq[b];
   }
-  seq.out_off[batch] = out;
+  seq->out_off[batch] = out;
   if (out == 0) return STRUCTKV_OK;
-  if (!idx) return fail(STRUCTKV_ERR_INVALID_ARG, "idx is NULL");
+  if (idx_needed && !idx) return fail(STRUCTKV_ERR_INVALID_ARG, "idx is NULL");
   if ((k_src == nullptr) != (k_dst == nullptr) || (v_src == nullptr) != (v_dst == nullptr))
     return fail(STRUCTKV_ERR_INVALID_ARG, "src/dst of a pair must both be given or both be NULL");
   if (!k_src && !v_src) return STRUCTKV_OK;
   const uintptr_t ptrs = (uintptr_t)k_src | (uintptr_t)v_src | (uintptr_t)k_dst | (uintptr_t)v_dst;
   if (ptrs & (uintptr_t)(elem_bytes - 1)) return fail(STRUCTKV_ERR_INVALID_ARG, "pointers not aligned to the element size");
-  const int64_t e = elem_bytes;
-  if (out * head_dim * e / 2 >= ((int64_t)1 << 31) - 4096)
+  if (out * head_dim * (int64_t)elem_bytes / 2 >= ((int64_t)1 << 31) - 4096)
     return fail(STRUCTKV_ERR_UNSUPPORTED, "too many rows for one launch (rows*head_dim*elem_bytes/2 must stay below 2^31)");
+  *nothing_to_do = false;
+  return STRUCTKV_OK;
+}
+
+structkv_status structkv_gather_kv(const void* k_src, const void* v_src, int64_t src_stride_head,
+                                   int64_t src_stride_tok, void* k_dst, void* v_dst, int64_t dst_stride_head,
+                                   int64_t dst_stride_tok, int32_t n_kv_heads, int32_t head_dim,
+                                   int32_t elem_bytes, int32_t batch, const int64_t* cu_seqlens,
+                                   const int64_t* rows_per_seq, const int32_t* idx, void* stream) {
+  clear_error();
+  SeqTable seq;
+  bool nothing = true;
+  structkv_status st = check_gather_args(k_src, v_src, src_stride_head, src_stride_tok, k_dst, v_dst, dst_stride_head,
+                                         dst_stride_tok, n_kv_heads, head_dim, elem_bytes, batch, cu_seqlens,
+                                         rows_per_seq, idx, true, &seq, &nothing);
+  if (st != STRUCTKV_OK || nothing) return st;
+  const int64_t e = elem_bytes;
   SKV_HIP_CHECK(launch_gather(k_src, v_src, src_stride_head * e, src_stride_tok * e, k_dst, v_dst,
                               dst_stride_head * e, dst_stride_tok * e, n_kv_heads, head_dim * elem_bytes, seq,
                               idx, (hipStream_t)stream));
   return STRUCTKV_OK;
+}
+
+size_t structkv_layer_step_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
+  const size_t a = structkv_workspace_bytes(shape, batch, total_tokens);
+  const size_t b = structkv_workspace_bytes(nullptr, batch, total_tokens);
+  if (!shape || a == 0 || b == 0) return 0;
+  return a + b;   // scoring scratch and selection scratch are live at the same time
+}
+
+namespace {
+// Everything a fused layer step derives from its arguments: validated once, used by both halves.
+struct LayerStepPlan {
+  SeqTable sel;          // cu, budgets, output offsets
+  SeqTable blocks;       // the selection's workgroups per sequence
+  SeqTable gseq;         // the row gather's table (fallback path)
+  TopkWs tws;
+  unsigned n_blocks = 0;
+  int64_t rows = 0;      // output entries in all
+  bool no_rows = true;
+  SelectFusion fuse{};
+  size_t score_bytes = 0;
+  int elem_bytes = 2;
+};
+
+// *done = true: nothing to enqueue (empty batch)
+structkv_status plan_layer_step(const structkv_shape* shape, const void* k, const void* v, int64_t kv_stride_head,
+                                int64_t kv_stride_tok, int32_t batch, const int64_t* cu_seqlens,
+                                const int64_t* k_per_seq, int32_t keep_tail, const float* indeg, int32_t* idx_out,
+                                void* k_dst, void* v_dst, int64_t dst_stride_head, int64_t dst_stride_tok,
+                                void* workspace, size_t workspace_bytes, LayerStepPlan* p, bool* done) {
+  *done = false;
+  structkv_status st = check_shape(shape);
+  if (st != STRUCTKV_OK) return st;
+  // the selection's arguments (budgets, window, output offsets) ...
+  st = check_topk_args(indeg, batch, cu_seqlens, k_per_seq, keep_tail, idx_out, &p->sel, &p->rows);
+  if (st != STRUCTKV_OK) return st;
+  if (batch == 0) { *done = true; return STRUCTKV_OK; }
+  // ... and the cache store's: rows_b = k_b + keep_tail
+  int64_t rows_per_seq[kMaxBatch];
+  for (int b = 0; b < batch; ++b) rows_per_seq[b] = k_per_seq[b] + keep_tail;
+  p->elem_bytes = shape->dtype == STRUCTKV_DTYPE_BF16 ? 2 : 4;
+  st = check_gather_args(k_dst ? k : nullptr, v_dst ? v : nullptr, kv_stride_head, kv_stride_tok, k_dst, v_dst,
+                         dst_stride_head, dst_stride_tok, shape->n_kv_heads, shape->head_dim, p->elem_bytes, batch,
+                         cu_seqlens, rows_per_seq, idx_out, false, &p->gseq, &p->no_rows);
+  if (st != STRUCTKV_OK) return st;
+  if (v_dst && !v) return fail(STRUCTKV_ERR_INVALID_ARG, "v_dst given without v");
+  if (k_dst && !k) return fail(STRUCTKV_ERR_INVALID_ARG, "k_dst given without k");
+  if (!workspace || ((uintptr_t)workspace & 255))
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  const int64_t total = p->sel.cu[batch];
+  p->score_bytes = structkv_workspace_bytes(shape, batch, total);
+  const size_t topk_bytes = topk_workspace_bytes(batch, total);
+  if (workspace_bytes < p->score_bytes + topk_bytes)
+    return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, a layer step needs %zu", workspace_bytes,
+                p->score_bytes + topk_bytes);
+  topk_plan(p->sel, keep_tail, (uint8_t*)workspace + p->score_bytes, &p->blocks, &p->tws, &p->n_blocks);
+  p->fuse.hist = p->tws.hist;
+  p->fuse.idx_out = idx_out;
+  p->fuse.keep_tail = keep_tail;
+  return STRUCTKV_OK;
+}
+
+structkv_status layer_finish_impl(const structkv_shape* shape, const LayerStepPlan& p, const void* k, const void* v,
+                                  int64_t kv_stride_head, int64_t kv_stride_tok, int32_t keep_tail, const float* indeg,
+                                  int32_t* idx_out, void* k_dst, void* v_dst, int64_t dst_stride_head,
+                                  int64_t dst_stride_tok, hipStream_t hs) {
+  if (p.rows == 0) return STRUCTKV_OK;
+  SKV_HIP_CHECK(launch_topk_rest(indeg, p.blocks, keep_tail, p.tws, p.n_blocks, idx_out, hs));
+  const int64_t e = p.elem_bytes;
+  if (!p.no_rows)
+    SKV_HIP_CHECK(launch_gather(k_dst ? k : nullptr, v_dst ? v : nullptr, kv_stride_head * e, kv_stride_tok * e, k_dst,
+                                v_dst, dst_stride_head * e, dst_stride_tok * e, shape->n_kv_heads,
+                                shape->head_dim * p.elem_bytes, p.gseq, idx_out, hs));
+  return STRUCTKV_OK;
+}
+}  // namespace
+
+structkv_status structkv_layer_begin(const structkv_shape* shape, const void* q_win, const void* k, const void* v,
+                                     int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                     const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                     float* indeg_out, float* centrality, float lambda, float inv_w,
+                                     float* entropy_out, float* entropy_per_head_out, int32_t* idx_out, void* k_dst,
+                                     void* v_dst, int64_t dst_stride_head, int64_t dst_stride_tok, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (centrality) {
+    if (!(lambda > 0.f && lambda <= 1.f)) return fail(STRUCTKV_ERR_INVALID_ARG, "lambda must be in (0,1]");
+    if (!(inv_w > 0.f) || !std::isfinite(inv_w)) return fail(STRUCTKV_ERR_INVALID_ARG, "inv_w must be > 0");
+    if ((uintptr_t)centrality & 3) return fail(STRUCTKV_ERR_INVALID_ARG, "centrality is not 4-byte aligned");
+    if (centrality == indeg_out) return fail(STRUCTKV_ERR_INVALID_ARG, "centrality must not alias indeg_out");
+  }
+  LayerStepPlan p;
+  bool done = false;
+  structkv_status st = plan_layer_step(shape, k, v, kv_stride_head, kv_stride_tok, batch, cu_seqlens, k_per_seq,
+                                       keep_tail, indeg_out, idx_out, k_dst, v_dst, dst_stride_head, dst_stride_tok,
+                                       workspace, workspace_bytes, &p, &done);
+  if (st != STRUCTKV_OK || done) return st;
+  ScoreOpts o;
+  o.centrality = centrality; o.lambda = lambda; o.inv_w = inv_w;
+  o.fuse = p.rows > 0 ? &p.fuse : nullptr;
+  return score_layer_impl(shape, q_win, k, kv_stride_head, kv_stride_tok, batch, cu_seqlens, indeg_out, entropy_out,
+                          entropy_per_head_out, workspace, p.score_bytes, stream, o, &p.sel);
+}
+
+structkv_status structkv_layer_finish(const structkv_shape* shape, const void* k, const void* v,
+                                      int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                      const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                      const float* indeg, int32_t* idx_out, void* k_dst, void* v_dst,
+                                      int64_t dst_stride_head, int64_t dst_stride_tok, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  clear_error();
+  LayerStepPlan p;
+  bool done = false;
+  structkv_status st = plan_layer_step(shape, k, v, kv_stride_head, kv_stride_tok, batch, cu_seqlens, k_per_seq,
+                                       keep_tail, indeg, idx_out, k_dst, v_dst, dst_stride_head, dst_stride_tok,
+                                       workspace, workspace_bytes, &p, &done);
+  if (st != STRUCTKV_OK || done) return st;
+  return layer_finish_impl(shape, p, k, v, kv_stride_head, kv_stride_tok, keep_tail, indeg, idx_out, k_dst, v_dst,
+                           dst_stride_head, dst_stride_tok, (hipStream_t)stream);
+}
+
+structkv_status structkv_layer_step(const structkv_shape* shape, const void* q_win, const void* k, const void* v,
+                                    int64_t kv_stride_head, int64_t kv_stride_tok, int32_t batch,
+                                    const int64_t* cu_seqlens, const int64_t* k_per_seq, int32_t keep_tail,
+                                    float* indeg_out, float* centrality, float lambda, float inv_w,
+                                    float* entropy_out, float* entropy_per_head_out, int32_t* idx_out, void* k_dst,
+                                    void* v_dst, int64_t dst_stride_head, int64_t dst_stride_tok, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  structkv_status st = structkv_layer_begin(shape, q_win, k, v, kv_stride_head, kv_stride_tok, batch, cu_seqlens,
+                                            k_per_seq, keep_tail, indeg_out, centrality, lambda, inv_w, entropy_out,
+                                            entropy_per_head_out, idx_out, k_dst, v_dst, dst_stride_head,
+                                            dst_stride_tok, workspace, workspace_bytes, stream);
+  if (st != STRUCTKV_OK) return st;
+  return structkv_layer_finish(shape, k, v, kv_stride_head, kv_stride_tok, batch, cu_seqlens, k_per_seq, keep_tail,
+                               indeg_out, idx_out, k_dst, v_dst, dst_stride_head, dst_stride_tok, workspace,
+                               workspace_bytes, stream);
 }
 
 structkv_status structkv_truncate_hidden(const void* h_src, int64_t src_stride_tok, void* h_dst,

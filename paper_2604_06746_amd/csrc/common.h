@@ -49,6 +49,34 @@ __device__ inline void merge_stats(float& M, float& Z, float& E, float M2, float
 }
 #endif
 
+// ---- selection (radix select on order-preserving keys) ---------------------------------------
+constexpr int kTopkBins = 2048;      // digits 0 and 1: 11 bits each; digit 2: the last 10 bits
+
+#ifdef __HIPCC__
+// order-preserving 32-bit key of a score: larger float <=> larger key; -0.0 orders as +0.0
+__device__ inline uint32_t score_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+#endif
+
+struct TopkWs {
+  uint32_t* hist;    // [B][3][kTopkBins]
+  uint32_t* state;   // [B][4]: digit 0, k left after it, 22-bit prefix, k left after it
+  uint32_t* suf;     // [blocks][1024]: suffix sums of the workgroup's last-digit histogram
+  uint32_t* meta;    // [blocks][2]: keys above the 22-bit prefix, keys equal to it
+};
+
+// What the scoring call's small kernels do for the selection that follows it in a fused layer step: the
+// combine kernel zeroes the digit histograms, the reduce kernel histograms the first digit of the scores
+// it has just formed and writes the kept window's indices.
+struct SelectFusion {
+  uint32_t* hist;        // [B][3][kTopkBins]; NULL = no fusion
+  int32_t* idx_out;
+  int keep_tail;
+};
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -79,17 +107,27 @@ hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const 
                              const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
                              float* stats, const float* lse2, float* colsum, int64_t total,
                              float* probs, int pass, hipStream_t st);
+// zero_words > 0: the kernel also clears that many 32-bit words at zero_ptr (the selection's histograms)
 hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                                const float* stats, float* lse2, float* row_ent, hipStream_t st);
+                                const float* stats, float* lse2, float* row_ent, uint32_t* zero_ptr,
+                                int64_t zero_words, hipStream_t st);
+// fuse != NULL: seq.k / seq.out_off must hold the selection's budgets and output offsets
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                                const float* colsum, int64_t total, float* indeg, const float* row_ent,
                                float* ent_head, float* entropy, float* centrality, float lambda, float inv_w,
-                               hipStream_t st);
+                               const SelectFusion* fuse, hipStream_t st);
 hipError_t launch_group_sums(const structkv_shape& s, const ScorePlan& p, const float* colsum, int64_t total,
                              float* groups, hipStream_t st);
 hipError_t launch_accumulate(float* c, const float* d, int64_t n, float lambda, float inv_w, hipStream_t st);
 hipError_t launch_topk(const float* scores, const SeqTable& seq, int keep_tail, int32_t* idx_out,
                        void* ws, hipStream_t st);
+// The same selection split for a fused layer step.  topk_plan: workgroups per sequence (into plan->chunk_start)
+// and the workspace carve.  launch_topk_rest: digits 1 and 2 and the ordered write, for a call whose histograms
+// were zeroed, whose first digit was histogrammed and whose window indices were written by the scoring kernels
+// (SelectFusion).
+void topk_plan(const SeqTable& seq_in, int keep_tail, void* wsp, SeqTable* plan, TopkWs* ws, unsigned* blocks);
+hipError_t launch_topk_rest(const float* scores, const SeqTable& plan, int keep_tail, const TopkWs& ws,
+                            unsigned blocks, int32_t* idx_out, hipStream_t st);
 size_t topk_workspace_bytes(int batch, int64_t total_tokens);
 // the library's own top-k scratch on the current device (structkv_select_topk_static); no allocation
 hipError_t topk_static_scratch(void** ptr, size_t* bytes);

@@ -20,9 +20,13 @@ constexpr int kCombRows = 32, kCombSlots = 32;
 
 __global__ __launch_bounds__(kCombRows* kCombSlots) void score_combine_kernel(
     SeqTable seq, int G, int R, int RPC, int RC, int WK, int64_t n_chunks, int row_blocks,
-    const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ row_ent) {
+    const float* __restrict__ stats, float* __restrict__ lse2, float* __restrict__ row_ent,
+    uint32_t* __restrict__ zero_ptr, int64_t zero_words) {
   short_kernel_priority();
   __shared__ float sM[kCombSlots / 2][kCombRows], sZ[kCombSlots / 2][kCombRows], sE[kCombSlots / 2][kCombRows];
+  // fused layer step: clear the digit histograms of the selection that follows the scoring
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < zero_words; i += (int64_t)gridDim.x * blockDim.x)
+    zero_ptr[i] = 0u;
   const int rblk = blockIdx.x % row_blocks;
   const int bg = blockIdx.x / row_blocks;
   const int b = bg / G, g = bg % G;
@@ -76,14 +80,25 @@ __global__ __launch_bounds__(kCombRows* kCombSlots) void score_combine_kernel(
 // exist to use every CU); planes are added in ascending order, eight loads in flight.
 // Workgroups b < B also finish Eq. 4 for sequence b.  With `cen` != NULL the kernel also applies
 // C <- lambda C + inv_w D with the arithmetic of accumulate_kernel (one fma on the rounded product).
-template <int V>
+// FUSED (a fused layer step, Eq. 13 follows Eq. 2 directly): the kernel also starts the selection on the
+// scores it has just formed -- the histogram of their first radix digit (what topk_hist0_kernel builds
+// from memory) and the kept window's indices.
+template <int V, bool FUSED>
 __global__ __launch_bounds__(256) void score_reduce_kernel(
     const float* __restrict__ colsum, int GRC, int64_t total, float* __restrict__ indeg,
     const float* __restrict__ row_ent, float* __restrict__ ent_head, float* __restrict__ entropy, int B,
-    int Hq, int w, float* __restrict__ cen, float lambda, float inv_w) {
+    int Hq, int w, float* __restrict__ cen, float lambda, float inv_w, SeqTable seq, SelectFusion fs) {
   short_kernel_priority();
   __shared__ float hsum[256];
+  __shared__ uint32_t h0[FUSED ? kTopkBins : 1];
   const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * V;
+  int b_wg = 0;   // FUSED: the sequence of the workgroup's first token; its digits are counted in LDS
+  if constexpr (FUSED) {
+    for (int i = threadIdx.x; i < kTopkBins; i += 256) h0[i] = 0u;
+    const int64_t first = min((int64_t)blockIdx.x * blockDim.x * V, total > 0 ? total - 1 : 0);
+    while (b_wg + 1 < B && first >= seq.cu[b_wg + 1]) ++b_wg;
+    __syncthreads();
+  }
   if (i0 < total) {   // V == 4 only when total % 4 == 0
     float a[V], c[V];
 #pragma unroll
@@ -125,12 +140,40 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(
       if constexpr (V == 4) *reinterpret_cast<float4*>(cen + i0) = make_float4(c[0], c[1], c[2], c[3]);
       else cen[i0] = c[0];
     }
+    if constexpr (FUSED) {
+      int b = b_wg;
+#pragma unroll
+      for (int j = 0; j < V; ++j) {
+        const int64_t i = i0 + j;
+        while (b + 1 < B && i >= seq.cu[b + 1]) ++b;
+        // only the prefix [0, n_b - keep_tail) of a sequence with a budget is searched
+        if (seq.k[b] > 0 && i - seq.cu[b] < seq.cu[b + 1] - seq.cu[b] - fs.keep_tail) {
+          const uint32_t digit = score_key(a[j]) >> 21;
+          if (b == b_wg) atomicAdd(&h0[digit], 1u);
+          else atomicAdd(&fs.hist[(size_t)b * 3 * kTopkBins + digit], 1u);
+        }
+      }
+    }
+  }
+  if constexpr (FUSED) {
+    __syncthreads();
+    uint32_t* gh = fs.hist + (size_t)b_wg * 3 * kTopkBins;
+    for (int i = threadIdx.x; i < kTopkBins; i += 256)
+      if (h0[i]) atomicAdd(&gh[i], h0[i]);
+    // the kept window: indices n_b - keep_tail .. n_b - 1 behind the k_b selected ones
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tail = fs.keep_tail;
+    for (int64_t u = gtid; u < (int64_t)B * tail; u += gsz) {
+      const int b = (int)(u / tail);
+      const int64_t i = u - (int64_t)b * tail;
+      fs.idx_out[seq.out_off[b] + seq.k[b] + i] = (int32_t)(seq.cu[b + 1] - seq.cu[b] - tail + i);
+    }
   }
   for (int b = blockIdx.x; b < B; b += gridDim.x) {   // uniform per workgroup
     // eight lanes share a head: each sums every eighth window row, then a fixed shuffle tree
     float part = 0.f;
-    for (int h0 = 0; h0 < Hq; h0 += 32) {
-      const int h = h0 + (threadIdx.x >> 3);
+    for (int h0i = 0; h0i < Hq; h0i += 32) {
+      const int h = h0i + (threadIdx.x >> 3);
       float s = 0.f;
       if (h < Hq) {
         const float* re = row_ent + ((int64_t)b * Hq + h) * w;
@@ -193,31 +236,33 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ c, 
 }  // namespace
 
 hipError_t launch_score_combine(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
-                                const float* stats, float* lse2, float* row_ent, hipStream_t st) {
+                                const float* stats, float* lse2, float* row_ent, uint32_t* zero_ptr,
+                                int64_t zero_words, hipStream_t st) {
   const int row_blocks = (int)ceil_div(p.R, kCombRows);
   const int64_t blocks = (int64_t)seq.batch * s.n_kv_heads * row_blocks;
   if (blocks == 0) return hipSuccess;
   hipLaunchKernelGGL(score_combine_kernel, dim3((unsigned)blocks), dim3(kCombRows * kCombSlots), 0, st, seq, s.n_kv_heads, p.R,
-                     p.RPC, p.RC, p.WK, p.n_chunks, row_blocks, stats, lse2, row_ent);
+                     p.RPC, p.RC, p.WK, p.n_chunks, row_blocks, stats, lse2, row_ent, zero_ptr, zero_words);
   return hipGetLastError();
 }
 
 hipError_t launch_score_reduce(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq,
                                const float* colsum, int64_t total, float* indeg, const float* row_ent,
                                float* ent_head, float* entropy, float* centrality, float lambda, float inv_w,
-                               hipStream_t st) {
+                               const SelectFusion* fuse, hipStream_t st) {
   const bool vec = (total % 4 == 0) && (((uintptr_t)indeg | (uintptr_t)colsum | (uintptr_t)centrality) & 15) == 0 &&
                    total >= (int64_t)4 * 256 * 1024;
   int64_t blocks = ceil_div(ceil_div(total, vec ? 4 : 1), 256);
   if (blocks == 0) blocks = 1;
-  if (vec)
-    hipLaunchKernelGGL(score_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                       s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
-                       s.window, centrality, lambda, inv_w);
-  else
-    hipLaunchKernelGGL(score_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st, colsum,
-                       s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,
-                       s.window, centrality, lambda, inv_w);
+  const bool fused = fuse != nullptr && fuse->hist != nullptr;
+  const SelectFusion fs = fused ? *fuse : SelectFusion{};
+#define SKV_REDUCE(V, F)                                                                                       \
+  hipLaunchKernelGGL((score_reduce_kernel<V, F>), dim3((unsigned)blocks), dim3(256), 0, st, colsum,            \
+                     s.n_kv_heads * p.CP, total, indeg, row_ent, ent_head, entropy, seq.batch, s.n_q_heads,    \
+                     s.window, centrality, lambda, inv_w, seq, fs)
+  if (vec) { if (fused) SKV_REDUCE(4, true); else SKV_REDUCE(4, false); }
+  else     { if (fused) SKV_REDUCE(1, true); else SKV_REDUCE(1, false); }
+#undef SKV_REDUCE
   return hipGetLastError();
 }
 

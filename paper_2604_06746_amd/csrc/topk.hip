@@ -29,25 +29,12 @@ constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kThreads = 256;
-constexpr int kBins = 2048;               // digits 0 and 1: 11 bits
+constexpr int kBins = kTopkBins;          // digits 0 and 1: 11 bits
 constexpr int kLowBins = 1024;            // digit 2: 10 bits
 constexpr int kTargetPerBlock = 2048;     // most scores a workgroup holds in registers (eight per thread)
 constexpr int kSmallTarget = 1024;        // share of a workgroup when the whole call is short: more, lighter
 constexpr int64_t kSmallTotal = 262144;   // workgroups shorten each kernel's serial part
 constexpr int kMaxBlocksPerSeq = 1024;    // beyond that a workgroup's share grows instead
-
-struct TopkWs {
-  uint32_t* hist;    // [B][3][kBins]
-  uint32_t* state;   // [B][4]: digit 0, k left after it, 22-bit prefix, k left after it
-  uint32_t* suf;     // [blocks][kLowBins]: suffix sums of the workgroup's last-digit histogram
-  uint32_t* meta;    // [blocks][2]: keys above the 22-bit prefix, keys equal to it
-};
-
-__device__ inline uint32_t score_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if (u == 0x80000000u) u = 0u;                         // -0.0 orders as +0.0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);    // larger float <=> larger key
-}
 
 // the calling workgroup's sequence and its contiguous share [lo, hi) of the prefix that is searched
 struct Share {
@@ -394,38 +381,52 @@ hipError_t topk_static_scratch(void** ptr, size_t* bytes) {
   return hipSuccess;
 }
 
+// workgroups per sequence (about `target` scores each, at most kMaxBlocksPerSeq; none where nothing is
+// selected) and the workspace carve
+void topk_plan(const SeqTable& seq_in, int keep_tail, void* wsp, SeqTable* plan, TopkWs* ws, unsigned* blocks) {
+  *plan = seq_in;
+  const int B = plan->batch;
+  const int target = share_target(plan->cu[B]);
+  plan->chunk_start[0] = 0;
+  for (int b = 0; b < B; ++b) {
+    const int64_t m = plan->cu[b + 1] - plan->cu[b] - keep_tail;
+    int64_t nblk = plan->k[b] > 0 ? ceil_div(m, target) : 0;
+    if (nblk > kMaxBlocksPerSeq) nblk = kMaxBlocksPerSeq;
+    plan->chunk_start[b + 1] = plan->chunk_start[b] + (int)nblk;
+  }
+  *blocks = (unsigned)plan->chunk_start[B];
+  const size_t nb = max_blocks(B, plan->cu[B]);   // blocks <= nb: sum of ceil(m_b / target) <= total / target + B
+  const size_t Bz = (size_t)(B > 0 ? B : 1);
+  uint8_t* p = (uint8_t*)wsp;
+  ws->hist = (uint32_t*)p;    p += align_up(sizeof(uint32_t) * 3 * Bz * kBins, 256);
+  ws->state = (uint32_t*)p;   p += align_up(sizeof(uint32_t) * 4 * Bz, 256);
+  ws->suf = (uint32_t*)p;     p += align_up(sizeof(uint32_t) * kLowBins * nb, 256);
+  ws->meta = (uint32_t*)p;
+}
+
+hipError_t launch_topk_rest(const float* scores, const SeqTable& plan, int keep_tail, const TopkWs& ws,
+                            unsigned blocks, int32_t* idx_out, hipStream_t st) {
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws);
+  hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws);
+  hipLaunchKernelGGL(topk_write_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws, idx_out);
+  return hipGetLastError();
+}
+
 // seq.out_off must hold the output offsets, seq.k the budgets.
 hipError_t launch_topk(const float* scores, const SeqTable& seq_in, int keep_tail, int32_t* idx_out,
                        void* wsp, hipStream_t st) {
-  SeqTable seq = seq_in;
-  const int B = seq.batch;
-  if (B == 0) return hipSuccess;
-  // workgroups per sequence: about `target` scores each, at most kMaxBlocksPerSeq
-  const int target = share_target(seq.cu[B]);
-  seq.chunk_start[0] = 0;
-  for (int b = 0; b < B; ++b) {
-    const int64_t m = seq.cu[b + 1] - seq.cu[b] - keep_tail;
-    int64_t nblk = seq.k[b] > 0 ? ceil_div(m, target) : 0;
-    if (nblk > kMaxBlocksPerSeq) nblk = kMaxBlocksPerSeq;
-    seq.chunk_start[b + 1] = seq.chunk_start[b] + (int)nblk;
-  }
-  const unsigned blocks = (unsigned)seq.chunk_start[B];
-  const size_t nb = max_blocks(B, seq.cu[B]);   // blocks <= nb: sum of ceil(m_b / target) <= total / target + B
+  if (seq_in.batch == 0) return hipSuccess;
+  SeqTable seq;
   TopkWs ws;
-  uint8_t* p = (uint8_t*)wsp;
-  ws.hist = (uint32_t*)p;    p += align_up(sizeof(uint32_t) * 3 * (size_t)B * kBins, 256);
-  ws.state = (uint32_t*)p;   p += align_up(sizeof(uint32_t) * 4 * (size_t)B, 256);
-  ws.suf = (uint32_t*)p;     p += align_up(sizeof(uint32_t) * kLowBins * nb, 256);
-  ws.meta = (uint32_t*)p;
-  hipLaunchKernelGGL(topk_init_kernel, dim3(4, B), dim3(kThreads), 0, st, seq, keep_tail, ws, idx_out);
-  if (blocks > 0) {
+  unsigned blocks = 0;
+  topk_plan(seq_in, keep_tail, wsp, &seq, &ws, &blocks);
+  hipLaunchKernelGGL(topk_init_kernel, dim3(4, seq.batch), dim3(kThreads), 0, st, seq, keep_tail, ws, idx_out);
+  if (blocks > 0)
     hipLaunchKernelGGL(topk_hist0_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
-    hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
-    hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws);
-    hipLaunchKernelGGL(topk_write_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, seq, keep_tail, ws,
-                       idx_out);
-  }
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_topk_rest(scores, seq, keep_tail, ws, blocks, idx_out, st);
 }
 
 }  // namespace skv

@@ -29,7 +29,8 @@ class LayerSweep:
         self.rows = sum(self.rows_per_seq)
         code = {torch.float32: B.STRUCTKV_DTYPE_F32, torch.bfloat16: B.STRUCTKV_DTYPE_BF16}[dtype]
         self.shape = B.make_shape(n_q_heads, n_kv_heads, head_dim, window, code, causal, scale)
-        ws_bytes = B.structkv_workspace_bytes(self.shape, self.batch, self.total)
+        # sized for the fused layer step (scoring and selection scratch live together); the separate calls need less
+        ws_bytes = B.structkv_layer_step_workspace_bytes(self.shape, self.batch, self.total)
         dev = torch.device(device)
         self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         # second score vector + a workspace of its own for the selection, used when selection and gather of one
@@ -97,8 +98,17 @@ class LayerSweep:
                              self.idx_kv, stream)
 
     def layer(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, slot: int = 0, stream=None) -> None:
-        """One pass of the hot path over one layer: score -> accumulate -> select -> gather."""
-        self.score_accumulate(q_win, k, stream)
+        """One pass of the hot path over one layer -- score -> accumulate -> select -> gather -- as ONE call of
+        the library (structkv_layer_step: same results as layer_separate_calls, fewer launches)."""
+        B.structkv_layer_step(self.shape, q_win, k, v, self.cu, self.k_per_seq, self.keep_tail, self.indeg,
+                              self.centrality, self.lam, 1.0 / self.w, self.entropy, self.entropy_per_head,
+                              self.idx_kv, self.k_cache[slot], self.v_cache[slot], self.workspace, stream)
+
+    def layer_separate_calls(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, slot: int = 0,
+                             stream=None) -> None:
+        """The same layer through the four entry points one by one."""
+        self.score(q_win, k, stream)
+        self.accumulate(stream)
         self.select_kv(stream)
         self.gather(k, v, slot, stream)
 
@@ -115,13 +125,16 @@ class LayerSweep:
                                ent=mk(chains[0]["ent"]), enth=mk(chains[0]["enth"])))
         return chains
 
-    def sweep_chains(self, layers, other_streams, slots=None) -> None:
+    def sweep_chains(self, layers, other_streams, slots=None, fused: bool = True) -> None:
         """All layers of a prefill as 1 + len(other_streams) chains: layer l runs on chain l mod n -- chain 0 is the
-        current stream -- as score -> accumulate -> select -> gather with the chain's own buffers.  Layers are
-        independent except for the recurrence C <- lambda C + D/w, which events keep in layer order, so the
-        results are those of layer() in a loop, bit for bit; one chain's short kernels run under another chain's
-        scoring kernels.  Afterwards indeg / idx_kv / entropy / entropy_per_head are the LAST layer's.  Ends with
-        all streams joined on the current one."""
+        current stream -- as the two halves of a fused layer step (score; select + gather) with the chain's own
+        buffers and the centrality update between them (`fused=False`: the four entry points one by one).  Layers
+        are independent except for that recurrence, C <- lambda C + D/w, which events keep in layer order, so the
+        results are those of layer() in a loop, bit for bit.  The update sits in the MIDDLE of a layer's kernels on
+        purpose: with the cross-stream wait at the end of a layer a captured graph ran the chains one after the
+        other (3.2 ms against 1.4 ms for the 32K configuration).  One chain's short
+        kernels run under another chain's scoring kernels.  Afterwards indeg / idx_kv / entropy / entropy_per_head
+        are the LAST layer's.  Ends with all streams joined on the current one."""
         a = torch.cuda.current_stream()
         streams = [a] + list(other_streams)
         n = len(streams)
@@ -134,16 +147,25 @@ class LayerSweep:
         last = 0
         for l, (q_win, k, v) in enumerate(layers):
             c, st = chain[l % n], streams[l % n]
-            B.structkv_score_layer(self.shape, q_win, k, self.cu, c["indeg"], c["ent"], c["enth"], c["ws"], st)
+            slot = l if slots is None else slots[l]
+            if fused:
+                B.structkv_layer_begin(self.shape, q_win, k, v, self.cu, self.k_per_seq, self.keep_tail, c["indeg"],
+                                       None, self.lam, 1.0 / self.w, c["ent"], c["enth"], c["idx"], self.k_cache[slot],
+                                       self.v_cache[slot], c["ws"], st)
+            else:
+                B.structkv_score_layer(self.shape, q_win, k, self.cu, c["indeg"], c["ent"], c["enth"], c["ws"], st)
             if acc_done is not None and n > 1:
                 st.wait_event(acc_done)
             B.structkv_accumulate_centrality(self.centrality, c["indeg"], self.lam, 1.0 / self.w, st)
             acc_done = torch.cuda.Event()
             acc_done.record(st)
-            B.structkv_select_topk(c["indeg"], self.cu, self.k_per_seq, self.keep_tail, c["idx"], c["tws"], st)
-            slot = l if slots is None else slots[l]
-            B.structkv_gather_kv(k, v, self.k_cache[slot], self.v_cache[slot], self.cu, self.rows_per_seq,
-                                 c["idx"], st)
+            if fused:
+                B.structkv_layer_finish(self.shape, k, v, self.cu, self.k_per_seq, self.keep_tail, c["indeg"], c["idx"],
+                                        self.k_cache[slot], self.v_cache[slot], c["ws"], st)
+            else:
+                B.structkv_select_topk(c["indeg"], self.cu, self.k_per_seq, self.keep_tail, c["idx"], c["tws"], st)
+                B.structkv_gather_kv(k, v, self.k_cache[slot], self.v_cache[slot], self.cu, self.rows_per_seq,
+                                     c["idx"], st)
             last = l % n
         for st in streams[1:]:
             done = torch.cuda.Event()

@@ -16,9 +16,18 @@ hipError_t launch_score_simt(const structkv_shape&, const ScorePlan&, const SeqT
                              int64_t, int64_t, float, float*, const float*, float*, int64_t, float*, int,
                              hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_score_combine(const structkv_shape&, const ScorePlan&, const SeqTable&, const float*, float*,
-                                float*, hipStream_t) { ++g_launches; return hipSuccess; }
+                                float*, uint32_t*, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_score_reduce(const structkv_shape&, const ScorePlan&, const SeqTable&, const float*, int64_t,
-                               float*, const float*, float*, float*, float*, float, float, hipStream_t) {
+                               float*, const float*, float*, float*, float*, float, float, const SelectFusion*,
+                               hipStream_t) {
+  ++g_launches; return hipSuccess;
+}
+void topk_plan(const SeqTable& seq_in, int, void* wsp, SeqTable* plan, TopkWs* ws, unsigned* blocks) {
+  *plan = seq_in;
+  *blocks = 1;
+  ws->hist = ws->state = ws->suf = ws->meta = (uint32_t*)wsp;
+}
+hipError_t launch_topk_rest(const float*, const SeqTable&, int, const TopkWs&, unsigned, int32_t*, hipStream_t) {
   ++g_launches; return hipSuccess;
 }
 hipError_t launch_group_sums(const structkv_shape&, const ScorePlan&, const float*, int64_t, float*, hipStream_t) {

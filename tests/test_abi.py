@@ -133,6 +133,22 @@ def test_invalid_arguments_are_rejected_on_the_host(B):
     assert stat(fake, 1, cu, (i64 * 1)(0), 0, fake, None) == B.STRUCTKV_OK   # nothing to do
     assert stat(None, 0, cu, None, 0, None, None) == B.STRUCTKV_OK
 
+    def step(ks=(i64 * 1)(10), tail=32, cen=ctypes.c_void_p(8192), lam=0.9, ws=None, kdst=fake, vsrc=fake, dtok=128, batch=1):
+        return lib.structkv_layer_step(ctypes.byref(ok_shape), fake, fake, vsrc, 100 * 128, 128, batch, cu, ks, tail,
+                                       fake, cen, lam, 0.1, fake, None, fake, kdst, fake, 50 * 128, dtok, ws, ws_bytes,
+                                       None)
+    assert step(ks=(i64 * 1)(90)) == B.STRUCTKV_ERR_INVALID_ARG            # k + window > n
+    assert step(ks=None) == B.STRUCTKV_ERR_INVALID_ARG
+    assert step(lam=0.0) == B.STRUCTKV_ERR_INVALID_ARG
+    assert step(cen=fake) == B.STRUCTKV_ERR_INVALID_ARG and "alias" in B.structkv_last_error()
+    assert step(dtok=64) == B.STRUCTKV_ERR_INVALID_ARG                     # destination rows overlap
+    assert step(vsrc=None) == B.STRUCTKV_ERR_INVALID_ARG                   # v_dst without v
+    assert step() == B.STRUCTKV_ERR_WORKSPACE                              # everything else valid: NULL workspace
+    assert step(cen=None) == B.STRUCTKV_ERR_WORKSPACE                      # the centrality is optional
+    assert step(batch=0) == B.STRUCTKV_OK
+    a, b_ = B.structkv_workspace_bytes(ok_shape, 1, 100), B.structkv_workspace_bytes(None, 1, 100)
+    assert B.structkv_layer_step_workspace_bytes(ok_shape, 1, 100) == a + b_
+
     blk = lib.structkv_block_scores
     assert blk(fake, 1, cu, 0, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
     assert blk(None, 1, cu, 16, fake, None) == B.STRUCTKV_ERR_INVALID_ARG
@@ -274,6 +290,13 @@ def test_host_planning_with_stub_launchers(B):
             assert lib.structkv_gather_kv(fake, fake, total * d, d, fake2, fake2, sum(rows) * d, d, G, d, 2, batch, cu,
                                           rows, fake, None) == B.STRUCTKV_OK, B.structkv_last_error()
             assert lib.structkv_block_scores(fake, batch, cu, 16, fake2, None) == B.STRUCTKV_OK
+            tail = w if 0 not in lens else 0
+            sneed = B.structkv_layer_step_workspace_bytes(shape, batch, total)
+            fake3 = ctypes.c_void_p(1 << 22)
+            assert lib.structkv_layer_step(ctypes.byref(shape), fake, fake, fake, total * d, d, batch, cu, ks, tail,
+                                           fake3, None, 0.9, 0.1, fake, None, fake, fake2, fake2,
+                                           (sum(rows) + batch * tail) * d, d, fake2, sneed, None) == B.STRUCTKV_OK, \
+                B.structkv_last_error()
         pneed = B.structkv_pivot_workspace_bytes(shape, 4096)
         cu1 = (i64 * 3)(0, 4096, 4096 + 100 + w)
         assert lib.structkv_score_layer_pivot(ctypes.byref(shape), fake, fake, 5000 * d, d, 2, cu1, 0.1, fake, fake, None,

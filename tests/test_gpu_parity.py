@@ -693,3 +693,101 @@ def test_graph_replays_equal_the_eager_sweep(sweep_mod, overlap):
         assert torch.equal(ref.k_cache, sw.k_cache) and torch.equal(ref.v_cache, sw.v_cache), rep
         assert torch.equal(ref.entropy, sw.entropy), rep
 
+
+
+# ------------------------------------------------------------------ the fused layer step (Alg. 1 lines 4, 6, 16, 17)
+
+def _both_ways(sweep_mod, wl, make_inputs, layers=2, keep_tail=None, ks=None):
+    """layer() (one structkv_layer_step call) against layer_separate_calls() (the four entry points): same bits."""
+    a, b = make_sweep(sweep_mod, wl), make_sweep(sweep_mod, wl)
+    for sw in (a, b):
+        if keep_tail is not None:
+            sw.keep_tail = keep_tail
+        if ks is not None:
+            sw.k_per_seq = list(ks)
+        sw.rows_per_seq = [k + sw.keep_tail for k in sw.k_per_seq]
+        sw.rows = sum(sw.rows_per_seq)
+        sw.idx_kv.fill_(-5); sw.k_cache.fill_(3.0); sw.v_cache.fill_(3.0); sw.workspace.fill_(0xCD)
+    for layer in range(layers):
+        q, k, v = make_inputs(layer)
+        a.layer(q, k, v)
+        b.layer_separate_calls(q, k, v)
+        torch.cuda.synchronize()
+        assert torch.equal(a.indeg, b.indeg) and torch.equal(a.centrality, b.centrality), layer
+        assert torch.equal(a.entropy, b.entropy) and torch.equal(a.entropy_per_head, b.entropy_per_head), layer
+        assert torch.equal(a.idx_kv, b.idx_kv), layer
+        assert torch.equal(a.k_cache, b.k_cache) and torch.equal(a.v_cache, b.v_cache), layer
+    return a
+
+
+@pytest.mark.parametrize("name", SMALL + ["c2_llama8b_32k", "c5_ragged_batch8"])
+def test_layer_step_equals_the_four_calls(sweep_mod, name):
+    wl = workloads.WORKLOADS[name]
+
+    def inputs(layer):
+        x = workloads.make_layer(wl, layer, "cuda")
+        return x.q_win, x.k, x.v
+    _both_ways(sweep_mod, wl, inputs, layers=min(wl.n_layers, 2))
+    torch.cuda.empty_cache()
+
+
+def test_layer_step_degenerate_batches(sweep_mod):
+    # empty sequences, zero budgets, no window, a budget that takes the whole prefix, all-equal scores (ties)
+    wl = workloads.Workload("t_degenerate", 2, 8, 2, 128, (0, 200, 0, 65, 3000, 0), 32, "bf16", (0, 20, 0, 0, 2968, 0), 0)
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+
+    def inputs(layer):
+        q = torch.randn(wl.batch, 8, 32, 128, generator=g, device="cuda").to(torch.bfloat16)
+        k = torch.randn(2, wl.total_tokens, 128, generator=g, device="cuda").to(torch.bfloat16)
+        v = torch.randn(2, wl.total_tokens, 128, generator=g, device="cuda").to(torch.bfloat16)
+        if layer == 1:
+            q.zero_()                     # uniform attention: every score equal, selection by index alone
+        return q, k, v
+    # (an empty sequence cannot keep a window: with keep_tail > 0 every sequence needs n_b >= keep_tail)
+    _both_ways(sweep_mod, wl, inputs, keep_tail=0)
+    _both_ways(sweep_mod, wl, inputs, keep_tail=0, ks=(0, 200, 0, 5, 1, 0))
+    _both_ways(sweep_mod, wl, inputs, keep_tail=0, ks=(0, 0, 0, 0, 0, 0))
+    # with the window kept: zero budgets (the window alone), the whole prefix, one token short of it
+    wl2 = workloads.Workload("t_degenerate_tail", 2, 8, 2, 128, (32, 200, 65, 3000), 32, "bf16", (0, 0, 33, 2968), 0)
+
+    def inputs2(layer):
+        q = torch.randn(wl2.batch, 8, 32, 128, generator=g, device="cuda").to(torch.bfloat16)
+        k = torch.randn(2, wl2.total_tokens, 128, generator=g, device="cuda").to(torch.bfloat16)
+        v = torch.randn(2, wl2.total_tokens, 128, generator=g, device="cuda").to(torch.bfloat16)
+        if layer == 1:
+            q.zero_()
+        return q, k, v
+    _both_ways(sweep_mod, wl2, inputs2)
+    _both_ways(sweep_mod, wl2, inputs2, ks=(0, 167, 32, 1))
+
+
+def test_layer_step_odd_head_dim(sweep_mod):
+    # head_dim 36 (72-byte rows: SIMT scoring, 4-byte gather units)
+    wl = workloads.Workload("t_d36", 2, 4, 2, 36, (900, 70), 16, "bf16", (40, 6), 0)
+    g = torch.Generator(device="cuda"); g.manual_seed(6)
+
+    def inputs(layer):
+        q = torch.randn(2, 4, 16, 36, generator=g, device="cuda").to(torch.bfloat16)
+        k = torch.randn(2, 970, 36, generator=g, device="cuda").to(torch.bfloat16)
+        v = torch.randn(2, 970, 36, generator=g, device="cuda").to(torch.bfloat16)
+        return q, k, v
+    _both_ways(sweep_mod, wl, inputs)
+
+
+def test_layer_step_rejects_bad_arguments(B, sweep_mod):
+    wl = workloads.S_BF16
+    sw = make_sweep(sweep_mod, wl)
+    x = workloads.make_layer(wl, 0, "cuda")
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.StructKVError) as e:
+        B.structkv_layer_step(sw.shape, x.q_win, x.k, x.v, sw.cu, sw.k_per_seq, sw.keep_tail, sw.indeg, sw.centrality,
+                              0.9, 1.0 / 32, sw.entropy, None, sw.idx_kv, sw.k_cache[0], sw.v_cache[0], small)
+    assert e.value.status == B.STRUCTKV_ERR_WORKSPACE
+    with pytest.raises(B.StructKVError) as e:
+        B.structkv_layer_step(sw.shape, x.q_win, x.k, x.v, sw.cu, [wl.seq_lens[0]], sw.keep_tail, sw.indeg, None,
+                              0.9, 1.0 / 32, sw.entropy, None, sw.idx_kv, sw.k_cache[0], sw.v_cache[0], sw.workspace)
+    assert e.value.status == B.STRUCTKV_ERR_INVALID_ARG
+    with pytest.raises(B.StructKVError) as e:
+        B.structkv_layer_step(sw.shape, x.q_win, x.k, x.v, sw.cu, sw.k_per_seq, sw.keep_tail, sw.indeg, sw.centrality,
+                              1.5, 1.0 / 32, sw.entropy, None, sw.idx_kv, sw.k_cache[0], sw.v_cache[0], sw.workspace)
+    assert e.value.status == B.STRUCTKV_ERR_INVALID_ARG
