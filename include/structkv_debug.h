@@ -27,7 +27,11 @@ structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_
  * structkv_score_layer with only some of its four kernels enqueued, so a caller can bracket each with
  * events.  step_mask bits: 1 = pass 1 (row statistics, Eq. 4), 2 = combine (lse, entropy per row),
  * 4 = pass 2 (column sums, Eq. 2), 8 = reduce (in-degree, entropy).  Steps read what earlier steps left
- * in the workspace; mask 15 is structkv_score_layer itself.  force_simt as above.
+ * in the workspace; mask 15 is structkv_score_layer itself.  Bit 16: go through a batch whose keys exceed 192 MB
+ * in groups of consecutive sequences that fit the memory-side cache -- pass 1, combine, pass 2 of a group back
+ * to back -- instead of one launch per kernel over the whole batch (same results, bit for bit; kept for
+ * measuring the two schedules: the grouped one fetches less from HBM in pass 2 and is slower).
+ * force_simt as above.
  */
 structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,
                                            int64_t k_stride_head, int64_t k_stride_tok, int32_t batch,

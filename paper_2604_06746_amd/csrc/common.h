@@ -93,7 +93,8 @@ struct ScorePlan {
   int CP;            // pass-2 column-sum planes per KV head (the waves of a workgroup add theirs up first)
   int kshare;        // consecutive groups that read the same K head (1 in ordinary scoring; the per-head
                      // scoring of the pivot metrics runs every query head as its own group: H_q/G)
-  int64_t n_chunks;  // sum over sequences of ceil(n_b / KC)
+  int64_t n_chunks;  // sum over sequences of ceil(n_b / KC): the stride of the per-chunk statistics
+  int64_t grid_chunks;  // key chunks covered by ONE launch (= n_chunks unless the batch is scored in groups)
   // workspace carve (byte offsets)
   size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;
 };

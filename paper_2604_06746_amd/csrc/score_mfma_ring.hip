@@ -540,7 +540,7 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
                            const void* k, int64_t ksh, int64_t kst, float c2, float* stats,
                            const float* lse2, float* colsum, int64_t total, float* probs, int pass,
                            hipStream_t st) {
-  const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.n_chunks;
+  const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.grid_chunks;
   dim3 g((unsigned)grid), blk(64 * NW);
   // pass 2: dynamic LDS for the column sums of the key chunk and the waves' parked sums
   const unsigned cs_bytes = (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
@@ -561,7 +561,7 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
                                   const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
                                   float* stats, const float* lse2, float* colsum, int64_t total,
                                   float* probs, int pass, hipStream_t st) {
-  if (p.n_chunks == 0) return hipSuccess;
+  if (p.grid_chunks == 0) return hipSuccess;
   // four or two waves (64-row row-chunks) per workgroup with a 4-tile ring when the KV group has more than
   // 64 rows; otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
 #define SKV_RING(d, nrb, nw, nbuf)                                                                      \

@@ -125,11 +125,11 @@ hipError_t launch_score_simt(const structkv_shape& s, const ScorePlan& p, const 
                              const void* q, const void* k, int64_t ksh, int64_t kst, float c2,
                              float* stats, const float* lse2, float* colsum, int64_t total,
                              float* probs, int pass, hipStream_t st) {
-  if (p.n_chunks == 0) return hipSuccess;
+  if (p.grid_chunks == 0) return hipSuccess;
   const int d = s.head_dim;
   const int TKS = d <= 128 ? 64 : 16;
   const size_t smem = sizeof(float) * ((size_t)kRows * d + (size_t)TKS * (d + 1) + (size_t)kRows * TKS);
-  const int64_t grid = (int64_t)s.n_kv_heads * p.RC * p.n_chunks;
+  const int64_t grid = (int64_t)s.n_kv_heads * p.RC * p.grid_chunks;
   dim3 g((unsigned)grid), blk(256);
   if (s.dtype == STRUCTKV_DTYPE_F32) {
     hipLaunchKernelGGL(score_simt_kernel<float>, g, blk, smem, st, (const float*)q, (const float*)k, ksh,

@@ -16,6 +16,9 @@ def main():
     ap.add_argument("--workload", default="c3_llama8b_128k")
     ap.add_argument("--layers", type=int, default=2)
     ap.add_argument("--copy-mib", type=int, default=256)
+    ap.add_argument("--cache-groups", action="store_true",
+                    help="score each layer through the measurement hook that goes through a batch in cache-sized "
+                         "groups of sequences (pass 1, combine, pass 2 of a group back to back)")
     args = ap.parse_args()
     import torch
 
@@ -30,7 +33,11 @@ def main():
     for l in range(args.layers):
         x = workloads.make_layer(wl, l, "cuda")
         torch.cuda.synchronize()
-        sw.layer(x.q_win, x.k, x.v)
+        if args.cache_groups:
+            B.structkv_debug_score_steps(sw.shape, x.q_win, x.k, sw.cu, sw.indeg, sw.entropy, sw.entropy_per_head,
+                                         sw.workspace, 15 | 16)
+        else:
+            sw.layer(x.q_win, x.k, x.v)
         torch.cuda.synchronize()
     # calibration copy: [1, rows, 128] bf16 rows of 256 B, identity indices
     rows = args.copy_mib * 1024 * 1024 // 256

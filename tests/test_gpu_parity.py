@@ -791,3 +791,42 @@ def test_layer_step_rejects_bad_arguments(B, sweep_mod):
         B.structkv_layer_step(sw.shape, x.q_win, x.k, x.v, sw.cu, sw.k_per_seq, sw.keep_tail, sw.indeg, sw.centrality,
                               1.5, 1.0 / 32, sw.entropy, None, sw.idx_kv, sw.k_cache[0], sw.v_cache[0], sw.workspace)
     assert e.value.status == B.STRUCTKV_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ cache-sized groups of sequences
+
+def test_grouped_scoring_is_bit_identical(B, sweep_mod, oracle):
+    # a batch whose keys (226 MB) exceed the memory-side cache can be scored group by group (pass 1, combine, pass 2
+    # of a group back to back; the measurement hook's bit 16); same plan, so the same bits as one launch per kernel
+    Hq, G, d, w = 32, 8, 128, 32
+    lens = [40000, 300, 0, 70000, 33]
+    g = torch.Generator(device="cuda"); g.manual_seed(21)
+    q = torch.randn(len(lens), Hq, w, d, generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn(G, sum(lens), d, generator=g, device="cuda").to(torch.bfloat16)
+    sw = sweep_mod.LayerSweep(Hq, G, d, w, torch.bfloat16, lens, [n // 20 for n in lens])
+    sw.keep_tail = 0
+    sw.workspace.fill_(0x5A)
+    sw.score(q, k)                                             # one launch per kernel
+    torch.cuda.synchronize()
+    a, ea, eh = sw.indeg.clone(), sw.entropy.clone(), sw.entropy_per_head.clone()
+    sw.indeg.fill_(-1.0); sw.entropy.fill_(-1.0); sw.entropy_per_head.fill_(-1.0); sw.workspace.fill_(0xA5)
+    # grouped: [40000, 300, 0], [70000, 33]
+    B.structkv_debug_score_steps(sw.shape, q, k, sw.cu, sw.indeg, sw.entropy, sw.entropy_per_head, sw.workspace, 15 | 16)
+    torch.cuda.synchronize()
+    assert torch.equal(a, sw.indeg) and torch.equal(ea, sw.entropy) and torch.equal(eh, sw.entropy_per_head)
+    # kernel by kernel over the groups gives the same bits as well
+    sw.indeg.fill_(-1.0); sw.workspace.fill_(0x11)
+    for mask in (1, 2, 4, 8):
+        B.structkv_debug_score_steps(sw.shape, q, k, sw.cu, sw.indeg, sw.entropy, sw.entropy_per_head, sw.workspace,
+                                     mask | 16)
+    torch.cuda.synchronize()
+    assert torch.equal(a, sw.indeg) and torch.equal(ea, sw.entropy)
+    # and against the oracle on the two short sequences (the long ones are covered by the full-size tests)
+    for b in (1, 4):
+        off = sum(lens[:b])
+        D, ent, _, _ = oracle.score_layer(to_oracle_array(q[b:b + 1]), to_oracle_array(k[:, off:off + lens[b]]), Hq, G, d, w,
+                                          [lens[b]])
+        assert_close_floor(a[off:off + lens[b]].cpu().numpy(), D, 1e-3, "indeg seq %d" % b)
+        assert_entropy(ea[b:b + 1].cpu().numpy(), ent, 1e-3)
+    assert float(ea[2]) == 0.0
+    torch.cuda.empty_cache()
