@@ -256,8 +256,10 @@ structkv_status structkv_block_scores(const float* scores, int32_t batch, const 
  * vector over the n_b keys of sequence b.  Per sequence:
  *   sparsity_out[b] = (1/H_q) sum_h ( sum of the k largest a_h[j] ),   k = ceil(top_frac * n_b) in double arithmetic (paper: 0.1)
  *   variance_out[b] = (1/H_q) sum_h (1/n_b) sum_j (a_h[j] - 1/n_b)^2
- * (0 for an empty sequence).  It re-scores the layer head by head through the same kernels, so it costs about
- * as much as scoring the layer twice; call it only on the layers where the detector is still running.
+ * (0 for an empty sequence).  With bf16 inputs, head_dim 64 or 128 and a window of 32 or 64 the per-head in-degrees
+ * come out of the scoring pass itself (its second pass keeps one column-sum plane per query head) and the call
+ * costs one scoring of the layer plus four short passes over those planes (a radix select for the top-k mass);
+ * other shapes are re-scored head by head, which costs about as much as scoring the layer twice.
  * q_win, k, strides, cu_seqlens, shape: as structkv_score_layer.  sparsity_out, variance_out: DEVICE fp32 [B].
  * workspace: structkv_pivot_workspace_bytes(shape, longest sequence) bytes, 256-byte aligned.
  */
@@ -270,7 +272,7 @@ structkv_status structkv_pivot_metrics(const structkv_shape* shape, const void* 
 
 /*
  * structkv_score_layer and structkv_pivot_metrics from ONE scoring of the layer, for the layers on which the
- * pivot detector is still running (paper Eq. 2, 4, 5, 6): the per-head scoring that the metrics need also yields
+ * pivot detector is still running (paper Eq. 2, 4, 5, 6): the scoring that the metrics need also yields
  * the in-degree and the entropies.  Outputs as in structkv_score_layer (indeg_out DEVICE fp32 [total],
  * entropy_out DEVICE fp32 [B], entropy_per_head_out DEVICE fp32 [B][H_q] or NULL) and structkv_pivot_metrics.
  * indeg_out sums the heads in another order than structkv_score_layer does: equal to it within fp32 rounding, not

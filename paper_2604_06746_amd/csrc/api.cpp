@@ -61,11 +61,12 @@ structkv_status check_cu(int32_t batch, const int64_t* cu, SeqTable* seq) {
 
 // Decide path, tiling and workspace layout.  `n_chunk_bound` < 0: exact from seq; otherwise an upper bound.
 void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t total, bool mfma_ok,
-               ScorePlan* p) {
+               ScorePlan* p, bool planes = false) {
   const int gs = s.n_q_heads / s.n_kv_heads;
   p->R = gs * s.window;
   p->kshare = 1;
   p->path = mfma_ok ? 0 : 1;
+  p->planes = 0;
   if (p->path == 0) {
     // MFMA kernels: one wave owns RPC = 32*RB <= 64 rows and a chunk of KC keys.  A KV group with more rows is
     // cut into row-chunks of 64 rows whose waves form one workgroup and share the key tiles: four waves for more
@@ -79,7 +80,12 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave, 4 two-wave
     // or 8 one-wave workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
     // (RPC*d*2 bytes per wave) stays small against the K stream
-    const int64_t kMaxKC = p->NW == 4 ? 2048 : (p->NW == 2 ? 1024 : 896);   // the kernels' LDS column-sum capacity
+    // per-head planes: a wave's RPC rows must be one head's window (w = RPC) or two (w = 32, RPC = 64)
+    if (planes && (s.window == p->RPC || (s.window == 32 && p->RPC == 64 && gs % 2 == 0)))
+      p->planes = p->RPC / s.window;
+    // the kernels' LDS column-sum capacity
+    const int64_t kMaxKC = p->planes ? (p->NW == 4 ? 1280 : 1024) / p->planes
+                                     : (p->NW == 4 ? 2048 : (p->NW == 2 ? 1024 : 896));
     const int64_t slots = 256 * (p->NW == 4 ? 3 : (p->NW == 2 ? 4 : 8));
     const int64_t wg_per_chunk = s.n_kv_heads * ceil_div(p->RC, p->NW);
     const int64_t chunks_per_round = slots / wg_per_chunk > 0 ? slots / wg_per_chunk : 1;
@@ -92,7 +98,7 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     if (kc < kc_min) kc = kc_min;
     if (kc > kMaxKC) kc = kMaxKC;
     p->KC = (int)kc;
-    p->CP = (int)ceil_div(p->RC, p->NW);
+    p->CP = p->planes ? p->RC * p->planes : (int)ceil_div(p->RC, p->NW);
   } else {
     p->RPC = 16; p->RB = 0; p->NW = 0; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
@@ -140,6 +146,9 @@ struct ScoreOpts {
   bool cache_groups = false;   // measurement hook: score a batch in cache-sized groups of sequences
   float* probs = nullptr;      // test hook: the attention rows themselves
   const SelectFusion* fuse = nullptr;   // fused layer step: the small kernels also start the selection
+  bool planes = false;         // pass 2 keeps one column-sum plane per 32-row block (per-head sums can follow)
+  uint32_t* zero_ptr = nullptr;   // words the combine kernel clears on the way (someone's histograms)
+  int64_t zero_words = 0;
 };
 
 structkv_status run_score(const structkv_shape* shape, const void* q_win, const void* k, int64_t ksh,
@@ -150,7 +159,8 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   const int B = seq.batch;
   const int64_t total = seq.cu[B];
   ScorePlan p;
-  make_plan(s, &seq, B, total, !o.force_simt && mfma_eligible(s, q_win, k, ksh, kst), &p);
+  make_plan(s, &seq, B, total, !o.force_simt && mfma_eligible(s, q_win, k, ksh, kst), &p, o.planes);
+  if (o.planes && !p.planes) return fail(STRUCTKV_ERR_UNSUPPORTED, "per-head planes need the MFMA kernels and a window of 32 or 64");
   p.kshare = o.kshare;   // s.n_kv_heads % kshare == 0 (the caller's business)
   if (p.total_bytes > ws_bytes)
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, p.total_bytes);
@@ -224,8 +234,8 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
       SKV_HIP_CHECK(pass(s, gp, sub, q_g, k, ksh, kst, c2, stats_g, lse2_g, colsum, total, nullptr, 1, st));
     if (mask & 2)
       SKV_HIP_CHECK(launch_score_combine(s, gp, sub, stats_g, lse2_g, row_ent_g,
-                                         o.fuse && gi == 0 ? o.fuse->hist : nullptr,
-                                         o.fuse && gi == 0 ? (int64_t)3 * kTopkBins * B : 0, st));
+                                         gi != 0 ? nullptr : (o.fuse ? o.fuse->hist : o.zero_ptr),
+                                         gi != 0 ? 0 : (o.fuse ? (int64_t)3 * kTopkBins * B : o.zero_words), st));
     if (mask & 4)
       SKV_HIP_CHECK(pass(s, gp, sub, q_g, k, ksh, kst, c2, stats_g, lse2_g, colsum, total, o.probs, 2, st));
     return STRUCTKV_OK;
@@ -756,6 +766,11 @@ bool pivot_carve(const structkv_shape& s, int64_t n_max, structkv_shape* sub, Pi
   c->score_ws_bytes = structkv_workspace_bytes(sub, 1, n_max);
   c->topk_ws_bytes = structkv_workspace_bytes(nullptr, hb, (int64_t)hb * n_max);
   if (c->score_ws_bytes == 0 || c->topk_ws_bytes == 0) return false;
+  {  // the scoring call with one column-sum plane per 32-row block (the path that needs no per-head re-scoring)
+    ScorePlan pp;
+    make_plan(s, nullptr, 1, n_max, true, &pp, true);
+    if (pp.total_bytes > c->score_ws_bytes) c->score_ws_bytes = align_up(pp.total_bytes, 256);
+  }
   size_t off = 0;
   c->off_heads = off;     off += align_up(sizeof(float) * (size_t)s.n_q_heads * N, 256);
   c->off_indeg = off;     off += align_up(sizeof(float) * N, 256);
@@ -821,14 +836,66 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
   const int Hq = shape->n_q_heads, gs = Hq / shape->n_kv_heads, w = shape->window, d = shape->head_dim;
   const size_t e = shape->dtype == STRUCTKV_DTYPE_BF16 ? 2 : 4;
   hipStream_t hs = (hipStream_t)stream;
+  // Where the bf16 MFMA kernels apply and a wave's rows are one head's window (or two), the metrics come out of the
+  // hot path's own scoring: pass 2 keeps one column-sum plane per query head -- the per-head in-degrees -- and
+  // nothing is scored twice.  Otherwise the layer is re-scored with every head as its own group.
+  bool from_planes = false;
+  if (mfma_eligible(*shape, q_win, k, k_stride_head, k_stride_tok) && Hq <= kMaxBatch) {
+    ScorePlan probe;
+    make_plan(*shape, nullptr, 1, n_max, true, &probe, true);
+    from_planes = probe.planes != 0 && probe.CP == gs;
+  }
   for (int b = 0; b < batch; ++b) {
     const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    const int64_t cu1[2] = {0, n};
+    const uint8_t* qs = (const uint8_t*)q_win + (size_t)b * Hq * w * d * e;
+    const uint8_t* ks = (const uint8_t*)k + (size_t)seq.cu[b] * k_stride_tok * e;
+    int64_t kk = (int64_t)std::ceil(top_frac * (double)n);   // the ceil(top_frac n) largest keys of every head
+    if (kk < 1) kk = 1;
+    if (kk > n) kk = n;
+    // (the planes path keeps its partial sums where the other path keeps indices: Hq x n words)
+    if (n > 0 && from_planes && 3 * (n / 1024 + 2) + 2 <= n) {
+      // selection scratch for the Hq heads as "sequences" of one call; its histograms are cleared by the
+      // scoring call's combine kernel and their first digit is filled by the kernel that forms the heads
+      SeqTable hseq;
+      memset(&hseq, 0, sizeof(hseq));
+      hseq.batch = Hq;
+      for (int i = 0; i <= Hq; ++i) hseq.cu[i] = (int64_t)i * n;
+      for (int i = 0; i < Hq; ++i) hseq.k[i] = (int32_t)kk;
+      SeqTable hplan;
+      TopkWs tws;
+      unsigned blocks = 0;
+      topk_plan(hseq, 0, w8 + c.off_topk_ws, &hplan, &tws, &blocks);
+      const int Pv = pivot_plane_shares(n), Pm = (int)(blocks / (unsigned)Hq);
+      float* var_part = (float*)idx;                       // the index scratch of the other path is free here
+      float* mass_part = var_part + (size_t)Hq * Pv;
+      float* tail = mass_part + (size_t)Hq * Pm * 2;
+      if ((int64_t)Pv + 2 * (int64_t)Pm + 2 > n) return fail(STRUCTKV_ERR_UNSUPPORTED, "pivot scratch too small");
+      ScoreOpts o;
+      o.planes = true;
+      o.zero_ptr = tws.hist;
+      o.zero_words = (int64_t)3 * kTopkBins * Hq;
+      st = score_layer_impl(shape, qs, ks, k_stride_head, k_stride_tok, 1, cu1,
+                            indeg_out ? indeg_out + seq.cu[b] : indeg, entropy_out ? entropy_out + b : ent,
+                            entropy_head_out ? entropy_head_out + (size_t)b * Hq : ent_h, w8 + c.off_score_ws,
+                            c.score_ws_bytes, stream, o);
+      if (st != STRUCTKV_OK) return st;
+      // where that call left its planes: the same plan, made again
+      ScorePlan pp;
+      SeqTable one;
+      memset(&one, 0, sizeof(one));
+      one.batch = 1; one.cu[1] = n;
+      make_plan(*shape, &one, 1, n, true, &pp, true);
+      const float* planes = (const float*)(w8 + c.off_score_ws + pp.off_colsum);   // [Hq][n]: plane g*gs + hl is head h
+      SKV_HIP_CHECK(launch_pivot_planes(planes, Hq, n, 1.0f / (float)w, tws.hist, var_part, hs));
+      SKV_HIP_CHECK(launch_topk_mass(planes, hplan, tws, blocks, Pm, mass_part, tail, hs));
+      SKV_HIP_CHECK(launch_pivot_finish_planes(var_part, Pv, mass_part, Pm, tail, Hq, n, 1.0f / (float)w, sparsity_out + b,
+                                               variance_out + b, hs));
+      continue;
+    }
     if (n > 0) {
       // per-head in-degree D_h [Hq][n]: one scoring call in which every query head is a group of its own
       // and the gs heads of a KV head read the same K head
-      const int64_t cu1[2] = {0, n};
-      const uint8_t* qs = (const uint8_t*)q_win + (size_t)b * Hq * w * d * e;
-      const uint8_t* ks = (const uint8_t*)k + (size_t)seq.cu[b] * k_stride_tok * e;
       ScoreOpts o;
       o.groups = heads; o.kshare = gs;
       st = score_layer_impl(&sub, qs, ks, k_stride_head, k_stride_tok, 1, cu1,
@@ -836,10 +903,6 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
                             entropy_head_out ? entropy_head_out + (size_t)b * Hq : ent_h, w8 + c.off_score_ws,
                             c.score_ws_bytes, stream, o);
       if (st != STRUCTKV_OK) return st;
-      // the ceil(top_frac n) largest keys of every head: heads are the "sequences" of one selection call
-      int64_t kk = (int64_t)std::ceil(top_frac * (double)n);
-      if (kk < 1) kk = 1;
-      if (kk > n) kk = n;
       for (int h0 = 0; h0 < Hq; h0 += kMaxBatch) {
         const int hb = Hq - h0 < kMaxBatch ? Hq - h0 : kMaxBatch;
         int64_t cuh[kMaxBatch + 1], kh[kMaxBatch];

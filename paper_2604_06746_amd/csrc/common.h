@@ -91,6 +91,9 @@ struct ScorePlan {
   int RB;            // MFMA path: 32-row blocks per wave (1, 2 or 4)
   int NW;            // MFMA path: waves (row-chunks) per workgroup sharing the key tiles (1, 2 or 4)
   int CP;            // pass-2 column-sum planes per KV head (the waves of a workgroup add theirs up first)
+  int planes;        // MFMA path, pass 2: 0, or column-sum planes per WAVE (1: a wave's rows are one query head's
+                     // window; 2: each of its two 32-row blocks is) instead of one per workgroup: CP = RC * planes =
+                     // query heads per KV head, and the planes are the per-head in-degrees
   int kshare;        // consecutive groups that read the same K head (1 in ordinary scoring; the per-head
                      // scoring of the pivot metrics runs every query head as its own group: H_q/G)
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC): the stride of the per-chunk statistics
@@ -139,6 +142,15 @@ hipError_t launch_pivot_heads(const float* heads, int H, int64_t n, const int32_
 hipError_t launch_zero_floats(float* p, int n, hipStream_t st);   // a fill kernel (safe inside a captured graph)
 hipError_t launch_pivot_finish(const float* part, int H, int64_t n, float inv_w, int valid, float* sparsity,
                                float* variance, hipStream_t st);
+// pivot metrics from the hot path's own scoring, whose pass 2 leaves the per-head in-degrees [H][n] in its
+// column-sum planes: first radix digit + variance partials, the top-k mass by radix select, the means over the heads
+int pivot_plane_shares(int64_t n);
+hipError_t launch_pivot_planes(const float* heads, int H, int64_t n, float inv_w, uint32_t* hist, float* part,
+                               hipStream_t st);
+hipError_t launch_topk_mass(const float* scores, const SeqTable& plan, const TopkWs& ws, unsigned blocks,
+                            int part_stride, float* part, float* tail, hipStream_t st);
+hipError_t launch_pivot_finish_planes(const float* var_part, int Pv, const float* mass_part, int Pm, const float* tail,
+                                      int H, int64_t n, float inv_w, float* sparsity, float* variance, hipStream_t st);
 hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);
 hipError_t launch_positions(const int64_t* pos_src, const SeqTable& seq, const int32_t* idx, int64_t* pos_dst,
                             hipStream_t st);

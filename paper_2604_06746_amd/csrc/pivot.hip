@@ -54,6 +54,82 @@ __global__ __launch_bounds__(256) void pivot_head_kernel(const float* __restrict
   }
 }
 
+// First pass over the per-head in-degrees that a scoring call leaves in its column-sum planes (pass 2 with one
+// plane per query head): the first radix digit of their selection and the variance partials.
+//   hist[h][digit of heads[h][j]] += 1;   part[h P + p] = sum over the workgroup's keys of (heads/w - 1/n)^2
+// grid (P, H): workgroup (p, h) takes keys [p*kPlaneShare, ...) of head h.
+constexpr int kPlaneShare = 2048;
+
+__global__ __launch_bounds__(256) void pivot_planes_kernel(const float* __restrict__ heads, int64_t n, float inv_w,
+                                                           uint32_t* __restrict__ hist, float* __restrict__ part) {
+  short_kernel_priority();
+  __shared__ uint32_t h0[kTopkBins];
+  __shared__ float sh[256];
+  const int p = blockIdx.x, h = blockIdx.y, P = gridDim.x;
+  const float* d = heads + (int64_t)h * n;
+  const int64_t lo = (int64_t)p * kPlaneShare;
+  float x[kPlaneShare / 256];
+#pragma unroll
+  for (int i = 0; i < kPlaneShare / 256; ++i) {   // loads first, the histogram's clearing under them
+    const int64_t j = lo + threadIdx.x + i * 256;
+    x[i] = j < n ? d[j] : 0.f;
+  }
+  for (int i = threadIdx.x; i < kTopkBins; i += 256) h0[i] = 0u;
+  __syncthreads();
+  const float mean = 1.0f / (float)n;
+  float v = 0.f;
+#pragma unroll
+  for (int i = 0; i < kPlaneShare / 256; ++i) {
+    if (lo + threadIdx.x + i * 256 < n) {
+      atomicAdd(&h0[score_key(x[i]) >> 21], 1u);
+      const float a = x[i] * inv_w - mean;
+      v = fmaf(a, a, v);
+    }
+  }
+  const float vs = block_sum(v, sh);   // its barriers also complete the LDS histogram
+  uint32_t* gh = hist + (size_t)h * 3 * kTopkBins;
+  for (int i = threadIdx.x; i < kTopkBins; i += 256)
+    if (h0[i]) atomicAdd(&gh[i], h0[i]);
+  if (threadIdx.x == 0) part[(int64_t)h * P + p] = vs;
+}
+
+// the means from the partials of the planes path: variance partials var_part [H][Pv] (pivot_planes_kernel),
+// mass partials mass_part [H][Pm][2] (second of each pair; topk_mass_kernel) and, per head, tail[2h] selected keys
+// that tie with the k-th largest, of value tail[2h+1].  Eight lanes share a head: each adds every eighth
+// partial, then a fixed shuffle tree; the heads are added in order by one thread.
+__global__ __launch_bounds__(256) void pivot_finish_planes_kernel(const float* __restrict__ var_part, int Pv,
+                                                                  const float* __restrict__ mass_part, int Pm,
+                                                                  const float* __restrict__ tail, int H, int64_t n,
+                                                                  float inv_w, float* __restrict__ sparsity,
+                                                                  float* __restrict__ variance) {
+  __shared__ float sv[32], sr[32];
+  float rt = 0.f, vt = 0.f;
+  const int sub = threadIdx.x & 7;
+  for (int h0 = 0; h0 < H; h0 += 32) {   // heads in rounds of 32
+    const int h = h0 + (int)(threadIdx.x >> 3);
+    float vs = 0.f, rs = 0.f;
+    if (h < H) {
+      for (int p = sub; p < Pv; p += 8) vs += var_part[(int64_t)h * Pv + p];
+      for (int p = sub; p < Pm; p += 8) rs += mass_part[((int64_t)h * Pm + p) * 2 + 1];
+    }
+    vs += __shfl_xor(vs, 1); vs += __shfl_xor(vs, 2); vs += __shfl_xor(vs, 4);
+    rs += __shfl_xor(rs, 1); rs += __shfl_xor(rs, 2); rs += __shfl_xor(rs, 4);
+    if (sub == 0) {
+      if (h < H) rs = fmaf(tail[2 * h], tail[2 * h + 1], rs);
+      sv[threadIdx.x >> 3] = vs / (float)n;
+      sr[threadIdx.x >> 3] = rs * inv_w;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int i = 0; i < 32 && h0 + i < H; ++i) { vt += sv[i]; rt += sr[i]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    *sparsity = rt / (float)H;
+    *variance = vt / (float)H;
+  }
+}
+
 // per head: the partial sums in slice order; then the means over the heads, in head order (valid == 0: zeros)
 __global__ __launch_bounds__(256) void pivot_finish_kernel(const float* __restrict__ part, int H, int P, int64_t n,
                                                            float inv_w, int valid, float* __restrict__ sparsity,
@@ -110,6 +186,23 @@ hipError_t launch_pivot_finish(const float* part, int H, int64_t n, float inv_w,
                                float* variance, hipStream_t st) {
   hipLaunchKernelGGL(pivot_finish_kernel, dim3(1), dim3(256), 0, st, part, H, pivot_slices(n), n, inv_w, valid,
                      sparsity, variance);
+  return hipGetLastError();
+}
+
+int pivot_plane_shares(int64_t n) { return (int)((n + kPlaneShare - 1) / kPlaneShare); }
+
+hipError_t launch_pivot_planes(const float* heads, int H, int64_t n, float inv_w, uint32_t* hist, float* part,
+                               hipStream_t st) {
+  if (H == 0 || n == 0) return hipSuccess;
+  hipLaunchKernelGGL(pivot_planes_kernel, dim3((unsigned)pivot_plane_shares(n), (unsigned)H), dim3(256), 0, st, heads,
+                     n, inv_w, hist, part);
+  return hipGetLastError();
+}
+
+hipError_t launch_pivot_finish_planes(const float* var_part, int Pv, const float* mass_part, int Pm, const float* tail,
+                                      int H, int64_t n, float inv_w, float* sparsity, float* variance, hipStream_t st) {
+  hipLaunchKernelGGL(pivot_finish_planes_kernel, dim3(1), dim3(256), 0, st, var_part, Pv, mass_part, Pm, tail, H, n,
+                     inv_w, sparsity, variance);
   return hipGetLastError();
 }
 

@@ -62,8 +62,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 // (one-wave workgroups: 896, so that eight of them -- 16 KB ring + 3.5 KB each -- still share a CU's 160 KB)
 template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896);
 
-// NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring
-template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP>
+// Pass 2 with one column-sum plane per QUERY HEAD instead of one per workgroup (the per-head in-degrees of the
+// pivot detector's metrics, Eq. 5-6): PPW planes per wave -- 1 when a wave's rows are one head's window, 2 when
+// each of its two 32-row blocks is.  Most keys a workgroup may then be given (its LDS holds NW*PPW sums per key;
+// 20 KB of them beside three 4-wave workgroups' rings, 8 KB beside four 2-wave ones, 4 KB beside eight 1-wave ones):
+template <int NW, int PPW> constexpr int kPlanesKeyCap = (NW == 4 ? 1280 : 1024) / PPW;
+
+// NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring; PPW > 0 (pass 2):
+// planes per wave as above, written to consecutive planes of `colsum`: plane g*RC*PPW + row-chunk*PPW + block
+template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP, int PPW = 0>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst, int kshare,
     SeqTable seq, int Hq, int G, int w, int causal, float c2, int R, int RC, int KC, int64_t n_chunks,
@@ -89,7 +96,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // the launcher passes their size) and are addressed by number, through asm: the ring stays the kernel's only LDS object,
   // whose reads the compiler then never orders behind the tile loads in flight (with the buffers as static
   // arrays, or with their addresses taken, it loses track and waits for ALL tile loads before LDS accesses).
-  constexpr int KCAP = PASS == 2 ? kKeyCap<NW> : 1;
+  constexpr bool PLANES = PPW > 0;
+  constexpr int KCAP = PASS == 2 ? (PLANES ? kPlanesKeyCap<NW, (PLANES ? PPW : 1)> : kKeyCap<NW>) : 1;
+  static_assert(!PLANES || (PASS == 2 && !DUMP && PPW <= NRB), "per-head planes are a pass-2 output");
   // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
   constexpr int VPM = PASS == 1 ? 8 : 4;
 
@@ -226,6 +235,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     win2[rb] = (rc * RPC + rb * 32) % w + 4 * lh;
   }
   float cs0 = 0.f, cs1 = 0.f;     // pass 2: column sum of this lane's key
+  float csp[PPW == 2 ? 2 : 1] = {};   // PPW == 2: the same per 32-row block (cs0 + cs1 of each block)
 
   auto mfma_block = [&](floatx16& acc, const bf16x8 (&kf)[KS], auto rb_tag) __attribute__((always_inline)) {
     constexpr int rb = decltype(rb_tag)::value;
@@ -313,6 +323,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
         }
         cs0 += pa; cs1 += pb;
       }
+      if constexpr (PPW == 2) { csp[rb] = cs0 + cs1; cs0 = 0.f; cs1 = 0.f; }
     }
   };
 
@@ -337,7 +348,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // immediate of the LDS instructions and costs no register), else a run-time one (its scalar part goes through
   // readfirstlane, stays in a scalar register and is added to the lane part at the point of use).
   auto flush_colsum = [&](int s_idx, auto ring_slot) __attribute__((always_inline)) {
-    if constexpr (PASS == 2 && NW > 1) if (wave == (s_idx % NW) && lh == 0) {
+    if constexpr (PASS == 2 && NW > 1 && !PLANES) if (wave == (s_idx % NW) && lh == 0) {
       constexpr bool RT = std::is_same<decltype(ring_slot), int>::value;
       uint32_t a = csbuf_lds + lane_x4_lo;
       if constexpr (RT) a = (uint32_t)__builtin_amdgcn_readfirstlane((int)(csbuf_lds + (uint32_t)(ring_slot * NW * 256))) + lane_x4_lo;
@@ -375,7 +386,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // of sub_tile: two copies get merged by the compiler into a store that has lost its alias information, and it
   // then waits for every outstanding tile load (which also write LDS) before it.
   auto park_colsum = [&](int jbase, auto ring_slot) __attribute__((always_inline)) {
-    if (PASS == 2) {
+    if (PASS == 2 && PLANES) {
+      // every wave keeps its own sums, one list per head: lane halves added here, no exchange between waves
+      constexpr int NP = PLANES ? PPW : 1;
+      const uint32_t a0 = csout_lds + (uint32_t)((wave * NP * KCAP + (jbase - key0 + l32)) * 4);
+#pragma unroll
+      for (int sp = 0; sp < NP; ++sp) {
+        float cs = PPW == 2 ? csp[sp] : cs0 + cs1;
+        cs += __shfl_xor(cs, 32);
+        const uint32_t a = a0 + (uint32_t)(sp * KCAP * 4);
+        const float val = live ? cs : 0.f;
+        if (lh == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(val) : "memory");
+      }
+      cs0 = 0.f; cs1 = 0.f;
+    } else if (PASS == 2) {
       float cs = cs0 + cs1;
       if (NW == 1) {
         cs += __shfl_xor(cs, 32);
@@ -496,7 +520,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   static_assert(NW == 1 || NBUF == 4, "the parked column sums use the ring slot number as tile mod 4");
   static_assert(NBUF == 2 || NBUF == 4, "key loop unrolled over the ring slots");
 
-  if (PASS == 2) {
+  if constexpr (PASS == 2 && PLANES) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+    // plane of (wave, block): g*RC*PPW + (row-chunk)*PPW + block; row-chunks beyond RC do not exist
+    constexpr int NP = PLANES ? PPW : 1;
+    const int rc0 = (int)(t % rcg) * NW;
+    for (int pl = 0; pl < NW * NP; ++pl) {
+      if (rc0 + pl / NP >= RC) break;
+      float* out = colsum + ((int64_t)g * RC * NP + (int64_t)rc0 * NP + pl) * total + tok0 + key0;
+      for (int i = threadIdx.x; i < key_end - key0; i += 64 * NW) {
+        float v;
+        const uint32_t a = csout_lds + (uint32_t)(pl * KCAP + i) * 4u;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a));
+        out[i] = v;
+      }
+    }
+  } else if (PASS == 2) {
     if (NW > 1) {
       // the asm LDS writes are unknown to the compiler, so the barriers' own fences do not wait for them
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -543,12 +583,19 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
   const int64_t grid = (int64_t)s.n_kv_heads * ceil_div(p.RC, NW) * p.grid_chunks;
   dim3 g((unsigned)grid), blk(64 * NW);
   // pass 2: dynamic LDS for the column sums of the key chunk and the waves' parked sums
-  const unsigned cs_bytes = (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
+  const int ppw = pass == 2 && probs == nullptr ? p.planes : 0;
+  const unsigned cs_bytes = ppw ? (unsigned)(NW * 1280 * 4)   // NW * PPW * kPlanesKeyCap<NW, PPW> * 4 at most
+                                : (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
   const unsigned dyn = pass == 1 ? 16u : cs_bytes;   // pass 1: the word of the rerun vote
 #define SKV_ARGS                                                                                        \
   g, blk, dyn, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
       s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs
   if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
+  else if (ppw == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false, 1>), SKV_ARGS);
+  else if (ppw == 2) {
+    if constexpr (NRB == 2) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false, 2>), SKV_ARGS);
+    else return hipErrorInvalidValue;
+  }
   else if (probs == nullptr) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false>), SKV_ARGS);
   else hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, true>), SKV_ARGS);
 #undef SKV_ARGS

@@ -335,6 +335,57 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
   }
 }
 
+// Sum of the k largest scores instead of their indices (the top-k mass of the pivot detector's sparsity, Eq. 5):
+// the last step of the same radix select.  Workgroup share as in the other kernels; writes the sum of its scores
+// ABOVE the k-th largest key T, in a fixed order, to part[(b*part_stride + rank of the workgroup)*2 + 1]; the
+// `need` selected scores that EQUAL T all have T's value, so the first workgroup of a sequence just records the
+// pair (need, value of T) in tail[2b], tail[2b+1] for whoever adds the partial sums up.
+__device__ inline float key_score(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+__global__ __launch_bounds__(kThreads) void topk_mass_kernel(const float* __restrict__ scores, SeqTable seq,
+                                                             TopkWs ws, int part_stride, float* __restrict__ part,
+                                                             float* __restrict__ tail) {
+  short_kernel_priority();
+  __shared__ uint32_t scan[4];
+  __shared__ uint32_t res[2];
+  __shared__ float red[kThreads];
+  const Share s = my_share(scores, seq, 0);
+  const int t = threadIdx.x;
+  const uint32_t* gh = ws.hist + (size_t)s.b * 3 * kBins;
+  float v[kPerThread];
+  const bool fast = preload_strided(s, v);
+  const uint32_t prefix = ws.state[s.b * 4 + 2], krem1 = ws.state[s.b * 4 + 3];
+  uint32_t t10, above2;
+  select_bin(gh + 2 * kBins, kLowBins, krem1, scan, res, &t10, &above2);
+  const uint32_t T = (prefix << 10) | t10;
+  float sum = 0.f;
+  if (fast) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+      if (s.lo + t + i * kThreads < s.hi && score_key(v[i]) > T) sum += v[i];
+  } else {
+    for (int64_t j = s.lo + t; j < s.hi; j += kThreads) {
+      const float x = s.sc[j];
+      if (score_key(x) > T) sum += x;
+    }
+  }
+  red[t] = sum;
+  __syncthreads();
+  for (int off = kThreads / 2; off > 0; off >>= 1) {
+    if (t < off) red[t] += red[t + off];
+    __syncthreads();
+  }
+  if (t == 0) {
+    part[((int64_t)s.b * part_stride + s.blk) * 2 + 1] = red[0];
+    if (s.blk == 0) {
+      tail[2 * s.b] = (float)(krem1 - above2);
+      tail[2 * s.b + 1] = key_score(T);
+    }
+  }
+}
+
 // upper bound of the workgroups one call launches
 inline int share_target(int64_t total_tokens) {
   return total_tokens <= kSmallTotal ? kSmallTarget : kTargetPerBlock;
@@ -410,6 +461,17 @@ hipError_t launch_topk_rest(const float* scores, const SeqTable& plan, int keep_
   hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws);
   hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws);
   hipLaunchKernelGGL(topk_write_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, keep_tail, ws, idx_out);
+  return hipGetLastError();
+}
+
+// digits 1 and 2, then the top-k MASS per sequence (see topk_mass_kernel); the first digit's histogram is the
+// caller's business.  Every sequence must have the same number of workgroups <= part_stride (equal lengths).
+hipError_t launch_topk_mass(const float* scores, const SeqTable& plan, const TopkWs& ws, unsigned blocks,
+                            int part_stride, float* part, float* tail, hipStream_t st) {
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, 0, ws);
+  hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, 0, ws);
+  hipLaunchKernelGGL(topk_mass_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, ws, part_stride, part, tail);
   return hipGetLastError();
 }
 

@@ -44,6 +44,15 @@ hipError_t topk_static_scratch(void** ptr, size_t* bytes) {
   *bytes = sizeof(host_stand_in);
   return hipSuccess;
 }
+int pivot_plane_shares(int64_t n) { return (int)((n + 2047) / 2048); }
+hipError_t launch_pivot_planes(const float*, int, int64_t, float, uint32_t*, float*, hipStream_t) {
+  ++g_launches; return hipSuccess;
+}
+hipError_t launch_topk_mass(const float*, const SeqTable&, const TopkWs&, unsigned, int, float*, float*, hipStream_t) {
+  ++g_launches; return hipSuccess;
+}
+hipError_t launch_pivot_finish_planes(const float*, int, const float*, int, const float*, int, int64_t, float, float*,
+                                      float*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_pivot_heads(const float*, int, int64_t, const int32_t*, int64_t, float, float*, hipStream_t) {
   ++g_launches; return hipSuccess;
 }

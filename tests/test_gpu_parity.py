@@ -429,7 +429,13 @@ def test_block_selection_and_block_gather_compose(B, oracle):
 
 # ------------------------------------------------------------------ pivot metrics (Eq. 5-6)
 
-@pytest.mark.parametrize("name,causal", [("s_bf16_w64", False), ("s_bf16_ragged", False), ("s_bf16_ragged", True),
+# shapes whose metrics come out of the hot path's own scoring (one column-sum plane per query head: a wave's 64 rows
+# are one head's window, or its two 32-row blocks are two heads'; 1, 2 and 4 waves per workgroup, an idle wave, two
+# workgroups per key chunk, d = 64) and shapes that are re-scored head by head (window 8, fp32)
+@pytest.mark.parametrize("name,causal", [("s_bf16_w64", False), ("s_bf16_w64", True), ("s_bf16_ragged", False),
+                                         ("s_bf16_ragged", True), ("s_bf16_d64", False), ("s_bf16_d64_r256", False),
+                                         ("s_bf16_r512", False), ("s_bf16_r192", False), ("s_bf16_gqa4", False),
+                                         ("s_bf16_r64", False),
                                          ("s_bf16_w8", False), ("s_f32_ragged", False), ("c1_tiny", False)])
 def test_pivot_metrics_match_oracle(B, sweep_mod, oracle, name, causal):
     wl = workloads.WORKLOADS[name]
