@@ -269,7 +269,7 @@ extern "C" {
 
 const char* structkv_last_error(void) { return g_err; }
 
-int32_t structkv_version(void) { return 100; }
+int32_t structkv_version(void) { return 200; }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;
