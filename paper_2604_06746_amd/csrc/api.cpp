@@ -146,7 +146,7 @@ struct ScoreOpts {
   bool cache_groups = false;   // measurement hook: score a batch in cache-sized groups of sequences
   float* probs = nullptr;      // test hook: the attention rows themselves
   const SelectFusion* fuse = nullptr;   // fused layer step: the small kernels also start the selection
-  bool planes = false;         // pass 2 keeps one column-sum plane per 32-row block (per-head sums can follow)
+  bool planes = false;         // pass 2 keeps one column-sum plane per query head (the pivot metrics' input)
   uint32_t* zero_ptr = nullptr;   // words the combine kernel clears on the way (someone's histograms)
   int64_t zero_words = 0;
 };
@@ -186,8 +186,9 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   // memory-side cache can be scored in groups of consecutive sequences whose keys fit it: pass 1, combine and
   // pass 2 of a group back to back, so that pass 2 finds in the cache what pass 1 has just streamed.  The plan
   // (keys per workgroup, summation order) stays the whole batch's, so every output is bit-identical to the
-  // ungrouped call.  Measured on the ragged batch of 8 (1.1 GB of keys per layer, window 32, where HBM binds):
-  // pass 2 does fetch less from HBM, but six groups cost 15 more launches per layer, each with its own ramp and
+  // ungrouped call.  Measured on the ragged batch of 8 (1.1 GB of keys per layer, window 32, where HBM binds): a
+  // pass 2 that follows its pass 1 directly is 13-15 % shorter for a lone sequence, but six groups cost 15 more
+  // launches per layer, each with its own ramp and
   // tail on a chip that one launch over the whole batch keeps full: 20.6 ms per sweep against 16.9 ms on one
   // stream (18.6 ms with every group planned as a batch of its own), no gain with layers on several streams,
   // whose K streams share the cache anyway.  So structkv_score_layer scores a batch with one launch per kernel.
