@@ -212,7 +212,9 @@ def main():
                 # while the library is the one that was profiled
                 if prof.get("_library_version") == B.structkv_version():
                     traffic = prof.get(wl.name, {}).get(dom)
-                    traffic_source = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of pmc_workload.py; not measured in this run)"
+                    if traffic is not None:
+                        traffic_source = ("profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                                          "pmc_workload.py; not measured in this run)")
             except Exception:
                 traffic = None
         score_us = sum(kern_us[k] for k in names[:4])
