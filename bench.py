@@ -25,6 +25,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 # Vector ALU: 256 CUs x 4 SIMDs, one 64-lane instruction per 4 cycles, 2.4 GHz.  v_exp_f32 issues at half that rate
 # on this chip (measured: 8.2 cycles per instruction), so it counts as two slots.
 VALU_PEAK_GSLOTS = 256 * 4 * 2.4 / 4.0
+# The same peak in flops: a slot is one 64-lane instruction, an fma counts 2 -> 78.6 TFLOP/s.  (The data sheet's
+# 157.3 TFLOP/s of fp32 vector rate assumes packed fp32, two fmas per lane and slot, which this build does not use.)
+VALU_PEAK_TFLOPS = VALU_PEAK_GSLOTS * 64 * 2 / 1e3
 VALU_SLOTS_PER_LOGIT = {"score_pass1": 5, "score_pass2": 4}   # scale-fma, exp (2), add, fma  /  mul, exp (2), add
 
 
@@ -197,9 +200,12 @@ def main():
                     "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_launch": k_bytes},
             "mfma": {"achieved": round(mfma_tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(mfma_tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_launch": qk_flops},
-            "alu": {"achieved": round(valu_gs, 1), "peak": VALU_PEAK_GSLOTS, "unit": "G issue slots/s",
+            "alu": {"achieved": round(valu_gs * 128 / 1e3, 2), "peak": round(VALU_PEAK_TFLOPS, 2), "unit": "TFLOP/s",
                     "frac": round(valu_gs / VALU_PEAK_GSLOTS, 4), "slots_per_logit": VALU_SLOTS_PER_LOGIT[dom],
-                    "slots_per_launch": valu_slots},
+                    "slots_per_launch": valu_slots, "achieved_Gslots": round(valu_gs, 1),
+                    "peak_Gslots": VALU_PEAK_GSLOTS,
+                    "note": "issue slots of the softmax's own instructions, one slot = one 64-lane instruction = "
+                            "128 flop at fma counting; un-packed fp32 peak (the data sheet's 157.3 assumes packed fp32)"},
         }
         # the unit that binds: the one the kernel uses the largest fraction of
         binds = max(units, key=lambda u: units[u]["frac"])
