@@ -30,7 +30,9 @@ structkv_status structkv_debug_probs(const structkv_shape* shape, const void* q_
  * in the workspace; mask 15 is structkv_score_layer itself.  Bit 16: go through a batch whose keys exceed 192 MB
  * in groups of consecutive sequences that fit the memory-side cache -- pass 1, combine, pass 2 of a group back
  * to back -- instead of one launch per kernel over the whole batch (same results, bit for bit; kept for
- * measuring the two schedules: the grouped one fetches less from HBM in pass 2 and is slower).
+ * measuring the two schedules: the grouped one fetches less from HBM in pass 2 and is slower).  Bit 32: fetch
+ * the K tiles with the other cache policy than the library's size rule picks (non-temporal below 256 MiB of K per
+ * layer, cached from there on); a cache policy changes no result.
  * force_simt as above.
  */
 structkv_status structkv_debug_score_steps(const structkv_shape* shape, const void* q_win, const void* k,

@@ -67,6 +67,8 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->kshare = 1;
   p->path = mfma_ok ? 0 : 1;
   p->planes = 0;
+  // a K of at least the memory-side cache's 256 MiB streams through the caches (see the kernel's NT parameter)
+  p->stream_k = p->path == 0 && total * s.n_kv_heads * s.head_dim * 2 >= ((int64_t)256 << 20);
   if (p->path == 0) {
     // MFMA kernels: one wave owns RPC = 32*RB <= 64 rows and a chunk of KC keys.  A KV group with more rows is
     // cut into row-chunks of 64 rows whose waves form one workgroup and share the key tiles: four waves for more
@@ -144,6 +146,7 @@ struct ScoreOpts {
   int kshare = 1;              // consecutive groups that read one K head (per-head scoring)
   bool force_simt = false;     // test hook: SIMT kernels even where the MFMA kernels apply
   bool cache_groups = false;   // measurement hook: score a batch in cache-sized groups of sequences
+  bool flip_stream_k = false;  // test hook: the other cache policy for the K tiles than the size rule picks
   float* probs = nullptr;      // test hook: the attention rows themselves
   const SelectFusion* fuse = nullptr;   // fused layer step: the small kernels also start the selection
   bool planes = false;         // pass 2 keeps one column-sum plane per query head (the pivot metrics' input)
@@ -162,6 +165,7 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
   make_plan(s, &seq, B, total, !o.force_simt && mfma_eligible(s, q_win, k, ksh, kst), &p, o.planes);
   if (o.planes && !p.planes) return fail(STRUCTKV_ERR_UNSUPPORTED, "per-head planes need the MFMA kernels and a window of 32 or 64");
   p.kshare = o.kshare;   // s.n_kv_heads % kshare == 0 (the caller's business)
+  if (o.flip_stream_k && p.path == 0) p.stream_k = !p.stream_k;
   if (p.total_bytes > ws_bytes)
     return fail(STRUCTKV_ERR_WORKSPACE, "workspace has %zu bytes, this call needs %zu", ws_bytes, p.total_bytes);
   if ((int64_t)s.n_kv_heads * p.RC * p.n_chunks >= ((int64_t)1 << 31))
@@ -226,6 +230,7 @@ structkv_status run_score(const structkv_shape* shape, const void* q_win, const 
         sub.chunk_start[i] = seq.chunk_start[b0 + i] - c0;    // launch-local key chunks
       }
       gp.grid_chunks = seq.chunk_start[b1] - c0;
+      gp.stream_k = 0;                                        // a group's keys are meant to stay in the cache
       q_g += (size_t)b0 * s.n_q_heads * s.window * s.head_dim * esz;
       stats_g += (size_t)c0 * p.WK * 3 * p.RPC;               // chunk c of row-chunk r sits at (r * n_chunks + c) * WK * 3 * RPC
       lse2_g += (size_t)b0 * s.n_q_heads * s.window;
@@ -270,7 +275,7 @@ extern "C" {
 
 const char* structkv_last_error(void) { return g_err; }
 
-int32_t structkv_version(void) { return 200; }
+int32_t structkv_version(void) { return 201; }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;
@@ -372,6 +377,7 @@ structkv_status structkv_debug_score_steps(const structkv_shape* shape, const vo
   ScoreOpts o;
   o.step_mask = step_mask & 15;
   o.cache_groups = (step_mask & 16) != 0;
+  o.flip_stream_k = (step_mask & 32) != 0;
   o.force_simt = force_simt != 0;
   return score_layer_impl(shape, q_win, k, k_stride_head, k_stride_tok, batch, cu_seqlens, indeg_out,
                           entropy_out, entropy_per_head_out, workspace, workspace_bytes, stream, o);

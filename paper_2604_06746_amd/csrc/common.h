@@ -98,6 +98,7 @@ struct ScorePlan {
                      // scoring of the pivot metrics runs every query head as its own group: H_q/G)
   int64_t n_chunks;  // sum over sequences of ceil(n_b / KC): the stride of the per-chunk statistics
   int64_t grid_chunks;  // key chunks covered by ONE launch (= n_chunks unless the batch is scored in groups)
+  int stream_k;      // MFMA path: 1 = fetch K with the non-temporal policy (K is larger than the memory-side cache)
   // workspace carve (byte offsets)
   size_t off_stats, off_lse, off_rowent, off_colsum, off_enthead, total_bytes;
 };

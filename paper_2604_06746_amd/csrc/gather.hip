@@ -11,6 +11,29 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 1;   // units per thread
 
+// Every row is read once and written once and neither is touched again by this kernel: the 16-byte units move with
+// the non-temporal policy, which keeps them from displacing what the next layer's scoring will read (measured on
+// back-to-back launches: 16.0 -> 14.2 us at 34 MB, 52.6 -> 47.2 us at 221 MB; non-temporal stores alone were slower
+// at 34 MB).  The builtins take clang's own vector types, not HIP's structs.
+typedef unsigned __attribute__((ext_vector_type(4))) u32x4;
+template <typename V> __device__ inline V load_once(const uint8_t* p) {
+  if constexpr (sizeof(V) == 16) {
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    V r; r.x = t[0]; r.y = t[1]; r.z = t[2]; r.w = t[3];
+    return r;
+  } else {
+    return *reinterpret_cast<const V*>(p);
+  }
+}
+template <typename V> __device__ inline void store_once(uint8_t* p, V v) {
+  if constexpr (sizeof(V) == 16) {
+    const u32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+  } else {
+    *reinterpret_cast<V*>(p) = v;
+  }
+}
+
 template <typename V, bool POW2>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     const uint8_t* __restrict__ src0, const uint8_t* __restrict__ src1, uint8_t* __restrict__ dst0,
@@ -35,13 +58,13 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
       const int64_t n = seq.cu[b + 1] - seq.cu[b];
       int64_t j = idx[row];
       if (j < 0 || j >= n) j = 0;
-      val[i] = *reinterpret_cast<const V*>(src + (seq.cu[b] + j) * sst + (int64_t)u * sizeof(V));
+      val[i] = load_once<V>(src + (seq.cu[b] + j) * sst + (int64_t)u * sizeof(V));
       doff[i] = (int64_t)row * dst_tok + (int64_t)u * sizeof(V);
     }
   }
 #pragma unroll
   for (int i = 0; i < kUnroll; ++i)
-    if (doff[i] >= 0) *reinterpret_cast<V*>(dst + doff[i]) = val[i];
+    if (doff[i] >= 0) store_once<V>(dst + doff[i], val[i]);
 }
 
 }  // namespace

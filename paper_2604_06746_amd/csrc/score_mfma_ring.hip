@@ -69,8 +69,11 @@ template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896
 template <int NW, int PPW> constexpr int kPlanesKeyCap = (NW == 4 ? 1280 : 1024) / PPW;
 
 // NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring; PPW > 0 (pass 2):
-// planes per wave as above, written to consecutive planes of `colsum`: plane g*RC*PPW + row-chunk*PPW + block
-template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP, int PPW = 0>
+// planes per wave as above, written to consecutive planes of `colsum`: plane g*RC*PPW + row-chunk*PPW + block.
+// NT: the key tiles are fetched with the non-temporal cache policy -- for a K larger than the 256 MB memory-side
+// cache, whose lines no later pass would find there anyway (measured: 4-8 % off both passes on a 1.1 GB K,
+// ~1 % on 256 MiB, and 3-6 % SLOWER on 64 MiB, where pass 2 and the gather do find pass 1's lines)
+template <int D, int NRB, int NW, int NBUF, int PASS, bool DUMP, int PPW = 0, bool NT = false>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int64_t ksh, int64_t kst, int kshare,
     SeqTable seq, int Hq, int G, int w, int causal, float c2, int R, int RC, int KC, int64_t n_chunks,
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     if (jbase + 32 <= ni) {
 #pragma unroll
       for (int ii = 0; ii < IPW; ++ii)
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(gbase + voff[ii]), (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(gbase + voff[ii]), (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, NT ? 2 : 0);
     } else {   // ragged tail: rows past the end re-read the last valid row (their logits are masked)
 #pragma unroll
       for (int ii = 0; ii < IPW; ++ii) {
@@ -208,7 +211,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
         const int seg = (unit % SEGS) ^ swz(key0u);
         const int key = min(key0u, ni - 1 - jbase);
         __builtin_amdgcn_global_load_lds((gbl_ptr_t)(gbase + (uint32_t)(key * kst + seg * 8) * 2u),
-                                         (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, 0);
+                                         (lds_ptr_t)(slot + ii * NW * 1024), 16, 0, NT ? 2 : 0);
       }
     }
   };
@@ -590,12 +593,15 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
 #define SKV_ARGS                                                                                        \
   g, blk, dyn, st, (const uint16_t*)q, (const uint16_t*)k, ksh, kst, p.kshare, seq, s.n_q_heads, s.n_kv_heads, \
       s.window, s.causal, c2, p.R, p.RC, p.KC, p.n_chunks, stats, lse2, colsum, total, probs
-  if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
+  if (pass == 1 && p.stream_k) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false, 0, true>), SKV_ARGS);
+  else if (pass == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 1, false>), SKV_ARGS);
   else if (ppw == 1) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false, 1>), SKV_ARGS);
   else if (ppw == 2) {
     if constexpr (NRB == 2) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false, 2>), SKV_ARGS);
     else return hipErrorInvalidValue;
   }
+  else if (probs == nullptr && p.stream_k)
+    hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false, 0, true>), SKV_ARGS);
   else if (probs == nullptr) hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, false>), SKV_ARGS);
   else hipLaunchKernelGGL((score_mfma_ring_kernel<D, NRB, NW, NBUF, 2, true>), SKV_ARGS);
 #undef SKV_ARGS

@@ -836,3 +836,25 @@ def test_grouped_scoring_is_bit_identical(B, sweep_mod, oracle):
         assert_entropy(ea[b:b + 1].cpu().numpy(), ent, 1e-3)
     assert float(ea[2]) == 0.0
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ cache policy of the K tiles
+
+@pytest.mark.parametrize("Hq,G,d,w,causal", [(2, 2, 64, 32, 0), (4, 2, 64, 32, 1), (8, 2, 64, 32, 0), (8, 2, 64, 64, 1),
+                                            (2, 2, 128, 32, 1), (4, 2, 128, 32, 0), (8, 2, 128, 32, 1), (8, 2, 128, 64, 0)])
+def test_streamed_k_tiles_give_the_same_bits(B, sweep_mod, Hq, G, d, w, causal):
+    # every tiling of the MFMA kernels (1, 2 or 4 waves per workgroup, one or two row blocks per wave, both head
+    # sizes) with the K tiles fetched non-temporally -- what the library does by itself from 256 MiB of K per layer
+    # on (the full-size tests) -- against the cached fetches these sizes get: a cache policy changes no bit
+    lens = [1500, 0, 4097, 333]
+    g = torch.Generator(device="cuda"); g.manual_seed(1000 * Hq + d + w)
+    q = torch.randn(len(lens), Hq, w, d, generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn(G, sum(lens), d, generator=g, device="cuda").to(torch.bfloat16)
+    sw = sweep_mod.LayerSweep(Hq, G, d, w, torch.bfloat16, lens, [n // 10 for n in lens], causal=bool(causal))
+    sw.score(q, k)
+    torch.cuda.synchronize()
+    a, ea, eh = sw.indeg.clone(), sw.entropy.clone(), sw.entropy_per_head.clone()
+    sw.indeg.fill_(-1.0); sw.entropy.fill_(-1.0); sw.entropy_per_head.fill_(-1.0); sw.workspace.fill_(0xA5)
+    B.structkv_debug_score_steps(sw.shape, q, k, sw.cu, sw.indeg, sw.entropy, sw.entropy_per_head, sw.workspace, 15 | 32)
+    torch.cuda.synchronize()
+    assert torch.equal(a, sw.indeg) and torch.equal(ea, sw.entropy) and torch.equal(eh, sw.entropy_per_head)
