@@ -71,24 +71,28 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
   p->stream_k = p->path == 0 && total * s.n_kv_heads * s.head_dim * 2 >= ((int64_t)256 << 20);
   if (p->path == 0) {
     // MFMA kernels: one wave owns RPC = 32*RB <= 64 rows and a chunk of KC keys.  A KV group with more rows is
-    // cut into row-chunks of 64 rows whose waves form one workgroup and share the key tiles: four waves for more
-    // than 128 rows (GQA 4 x w 64 = 256; at 168 registers three such waves fit a SIMD), two waves for 65..128
-    // rows.  Waves of 64 rows beat waves of 128 rows (256 registers, two per SIMD) by 6 % at 256 rows and by
-    // 20-25 % at 128 rows: more waves hide more of the MFMA -> softmax latency.
-    p->RB = p->R > 32 ? 2 : 1;
+    // cut into row-chunks whose waves form one four-wave workgroup and share the key tiles.  More than 128 rows
+    // (GQA 4 x w 64 = 256): row-chunks of 64 rows; at 168 registers three such waves fit a SIMD, and waves of 64
+    // rows beat waves of 128 rows (256 registers, two per SIMD) by 6 %: more waves hide more of the MFMA -> softmax
+    // latency.  65..128 rows (GQA 4 x w 32): row-chunks of 32 rows, again four waves -- against two waves of 64
+    // rows twice as many waves for the same keys per workgroup (a 32K-token layer then puts two waves on every
+    // SIMD instead of one: both passes -20 %) and a workgroup may take 2048 keys instead of 1024, so that sizes
+    // between whole rounds of resident workgroups quantise better (48K..512K tokens: -2 % .. -10 %, except
+    // exactly 128K, one full round either way: +2 %).  With 256 rows, 32-row waves LOSE 10-20 % (each wave reads
+    // the whole key tile from LDS for half the rows).
+    p->RB = (p->R > 32 && p->R <= 64) || p->R > 128 ? 2 : 1;
     p->RPC = 32 * p->RB; p->WK = 1;
     p->RC = (int)ceil_div(p->R, p->RPC);
-    p->NW = p->RC > 2 ? 4 : (p->RC > 1 ? 2 : 1);
-    // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave, 4 two-wave
-    // or 8 one-wave workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
+    p->NW = p->RC > 1 ? 4 : 1;
+    // keys per workgroup: whole rounds of resident workgroups over the chip (256 CUs x 3 four-wave or 8 one-wave
+    // workgroups), at most kMaxKC keys each, and at least 256 so that loading the query operands
     // (RPC*d*2 bytes per wave) stays small against the K stream
     // per-head planes: a wave's RPC rows must be one head's window (w = RPC) or two (w = 32, RPC = 64)
     if (planes && (s.window == p->RPC || (s.window == 32 && p->RPC == 64 && gs % 2 == 0)))
       p->planes = p->RPC / s.window;
     // the kernels' LDS column-sum capacity
-    const int64_t kMaxKC = p->planes ? (p->NW == 4 ? 1280 : 1024) / p->planes
-                                     : (p->NW == 4 ? 2048 : (p->NW == 2 ? 1024 : 896));
-    const int64_t slots = 256 * (p->NW == 4 ? 3 : (p->NW == 2 ? 4 : 8));
+    const int64_t kMaxKC = p->planes ? (p->NW == 4 ? 1280 : 1024) / p->planes : (p->NW == 4 ? 2048 : 896);
+    const int64_t slots = 256 * (p->NW == 4 ? 3 : 8);
     const int64_t wg_per_chunk = s.n_kv_heads * ceil_div(p->RC, p->NW);
     const int64_t chunks_per_round = slots / wg_per_chunk > 0 ? slots / wg_per_chunk : 1;
     const int64_t rounds = ceil_div(total > 0 ? total : 1, chunks_per_round * kMaxKC);
@@ -275,7 +279,7 @@ extern "C" {
 
 const char* structkv_last_error(void) { return g_err; }
 
-int32_t structkv_version(void) { return 201; }
+int32_t structkv_version(void) { return 202; }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;

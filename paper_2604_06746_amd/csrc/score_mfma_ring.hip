@@ -8,10 +8,10 @@
 // waves of 128 rows (256 registers); a ds_read_b128 stream sustains ~64 B/clk per CU, so each 1 KB
 // operand read from LDS must serve at least 2 MFMAs; HBM latency needs ~60 KB of loads in flight per CU.
 // Hence:
-//   * a wave owns a row-chunk of 64 query rows (2 blocks of 32; 32 rows for tiny KV groups) as MFMA
+//   * a wave owns a row-chunk of 64 query rows (2 blocks of 32) or of 32 rows as MFMA
 //     operands in registers for the whole kernel, and reads each key operand from LDS once per 32-key tile;
-//   * a KV group of 256 rows (GQA 4 x window 64) is four row-chunks = the four waves of a workgroup (128
-//     rows: two waves), which share the LDS tiles, so K crosses HBM -> L2 -> LDS once per pass;
+//   * a KV group of 256 rows (GQA 4 x window 64) is four row-chunks of 64 rows = the four waves of a workgroup
+//     (128 rows: four row-chunks of 32), which share the LDS tiles, so K crosses HBM -> L2 -> LDS once per pass;
 //   * tiles are fetched with global_load_lds_dwordx4 (16 B per lane, lane L lands at base + 16 L), three
 //     tiles ahead, into an XOR-swizzled layout that makes the operand reads bank-conflict free;
 //   * inside a wave the MFMAs of row block rb+1 are issued under the softmax arithmetic of row block rb.
@@ -60,12 +60,12 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // most keys a workgroup may be given (pass 2 keeps one fp32 column sum per key in LDS)
 // (one-wave workgroups: 896, so that eight of them -- 16 KB ring + 3.5 KB each -- still share a CU's 160 KB)
-template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : (NW == 2 ? 1024 : 896);
+template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : 896;
 
 // Pass 2 with one column-sum plane per QUERY HEAD instead of one per workgroup (the per-head in-degrees of the
 // pivot detector's metrics, Eq. 5-6): PPW planes per wave -- 1 when a wave's rows are one head's window, 2 when
 // each of its two 32-row blocks is.  Most keys a workgroup may then be given (its LDS holds NW*PPW sums per key;
-// 20 KB of them beside three 4-wave workgroups' rings, 8 KB beside four 2-wave ones, 4 KB beside eight 1-wave ones):
+// 20 KB of them beside three 4-wave workgroups' rings, 4 KB beside eight 1-wave ones):
 template <int NW, int PPW> constexpr int kPlanesKeyCap = (NW == 4 ? 1280 : 1024) / PPW;
 
 // NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring; PPW > 0 (pass 2):
@@ -615,17 +615,17 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
                                   float* stats, const float* lse2, float* colsum, int64_t total,
                                   float* probs, int pass, hipStream_t st) {
   if (p.grid_chunks == 0) return hipSuccess;
-  // four or two waves (64-row row-chunks) per workgroup with a 4-tile ring when the KV group has more than
-  // 64 rows; otherwise single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
+  // four waves per workgroup (row-chunks of 64 rows for a KV group of more than 128 rows, of 32 rows for 65..128)
+  // with a 4-tile ring; up to 64 rows: single-wave workgroups with a 2-tile ring (eight of them share a CU's LDS)
 #define SKV_RING(d, nrb, nw, nbuf)                                                                      \
   if (s.head_dim == d && p.RB == nrb && p.NW == nw)                                                      \
     return launch_ring_cfg<d, nrb, nw, nbuf>(s, p, seq, q, k, ksh, kst, c2, stats, lse2, colsum, total, probs, pass, st)
   SKV_RING(128, 2, 4, 4);
-  SKV_RING(128, 2, 2, 4);
+  SKV_RING(128, 1, 4, 4);
   SKV_RING(128, 2, 1, 2);
   SKV_RING(128, 1, 1, 2);
   SKV_RING(64, 2, 4, 4);
-  SKV_RING(64, 2, 2, 4);
+  SKV_RING(64, 1, 4, 4);
   SKV_RING(64, 2, 1, 2);
   SKV_RING(64, 1, 1, 2);
 #undef SKV_RING

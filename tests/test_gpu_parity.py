@@ -33,7 +33,7 @@ def sweep_mod():
 
 
 SMALL = ["s_bf16_gqa4", "s_bf16_w64", "s_bf16_d64", "s_bf16_ragged", "s_bf16_r192", "s_bf16_r160", "s_bf16_r512",
-         "s_bf16_d64_r256", "s_bf16_w8", "s_bf16_r64", "s_f32_w8", "s_f32_ragged", "c1_tiny"]
+         "s_bf16_d64_r256", "s_bf16_w8", "s_bf16_r64", "s_bf16_r96", "s_bf16_r120", "s_f32_w8", "s_f32_ragged", "c1_tiny"]
 
 
 # ------------------------------------------------------------------ attention rows (MFMA lane layout)
