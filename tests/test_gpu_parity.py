@@ -33,7 +33,7 @@ def sweep_mod():
 
 
 SMALL = ["s_bf16_gqa4", "s_bf16_w64", "s_bf16_d64", "s_bf16_ragged", "s_bf16_r192", "s_bf16_r160", "s_bf16_r512",
-         "s_bf16_d64_r256", "s_bf16_w8", "s_bf16_r64", "s_bf16_r96", "s_bf16_r120", "s_f32_w8", "s_f32_ragged", "c1_tiny"]
+         "s_bf16_d64_r256", "s_bf16_w8", "s_bf16_r64", "s_bf16_r96", "s_bf16_r120", "s_bf16_r192_w32", "s_f32_w8", "s_f32_ragged", "c1_tiny"]
 
 
 # ------------------------------------------------------------------ attention rows (MFMA lane layout)
@@ -430,12 +430,14 @@ def test_block_selection_and_block_gather_compose(B, oracle):
 # ------------------------------------------------------------------ pivot metrics (Eq. 5-6)
 
 # shapes whose metrics come out of the hot path's own scoring (one column-sum plane per query head: a wave's 64 rows
-# are one head's window, or its two 32-row blocks are two heads'; 1, 2 and 4 waves per workgroup, an idle wave, two
-# workgroups per key chunk, d = 64) and shapes that are re-scored head by head (window 8, fp32)
+# are one head's window, or its two 32-row blocks are two heads', or its 32 rows are; 1 and 4 waves per workgroup, an
+# idle wave, two workgroups per key chunk, d = 64) and shapes that are re-scored head by head (windows of 8 and 24
+# rows, which are no whole row block; fp32)
 @pytest.mark.parametrize("name,causal", [("s_bf16_w64", False), ("s_bf16_w64", True), ("s_bf16_ragged", False),
                                          ("s_bf16_ragged", True), ("s_bf16_d64", False), ("s_bf16_d64_r256", False),
                                          ("s_bf16_r512", False), ("s_bf16_r192", False), ("s_bf16_gqa4", False),
-                                         ("s_bf16_r64", False),
+                                         ("s_bf16_r64", False), ("s_bf16_r192_w32", False), ("s_bf16_r96", False),
+                                         ("s_bf16_r120", False),
                                          ("s_bf16_w8", False), ("s_f32_ragged", False), ("c1_tiny", False)])
 def test_pivot_metrics_match_oracle(B, sweep_mod, oracle, name, causal):
     wl = workloads.WORKLOADS[name]

@@ -141,6 +141,8 @@ S_BF16_W8 = _register(Workload("s_bf16_w8", 2, 8, 2, 128, (1234, 77), 8, "bf16",
 S_BF16_R64 = _register(Workload("s_bf16_r64", 2, 4, 2, 128, (1800,), 32, "bf16", (90,), 3, "all"))
 # 65..128 rows run as four waves of 32 rows: 3 x 32 = 96 rows (one idle wave) and 5 x 24 = 120 rows (heads straddle waves)
 S_BF16_R96 = _register(Workload("s_bf16_r96", 2, 6, 2, 128, (1700, 45), 32, "bf16", (80, 2), 3, "all"))
+# 6 heads x 32 rows = 192 rows in 64-row waves: each of a wave's two 32-row blocks is one head's window
+S_BF16_R192_W32 = _register(Workload("s_bf16_r192_w32", 2, 12, 2, 128, (1400, 200), 32, "bf16", (70, 10), 3, "all"))
 S_BF16_R120 = _register(Workload("s_bf16_r120", 2, 10, 2, 64, (1203,), 24, "bf16", (60,), 3, "all"))
 S_F32_W8 = _register(Workload("s_f32_w8", 2, 4, 2, 64, (777,), 8, "f32", (50,), 3, "all"))
 S_F32_RAGGED = _register(Workload("s_f32_ragged", 2, 8, 8, 64, (300, 40, 513), 32, "f32", (15, 2, 25), 2, "all"))
