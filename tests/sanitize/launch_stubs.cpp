@@ -1,17 +1,42 @@
 // Stand-ins for the kernel launchers of libstructkv, for the host-only sanitizer build of its C ABI:
 // api.cpp is compiled with -fsanitize=address,undefined and linked against these instead of the HIP
 // kernels, so that argument validation, work planning and workspace carving run under the sanitizers
-// on a machine without a GPU.  Each stub checks nothing and launches nothing; it only counts the call.
+// on a machine without a GPU.  The stubs launch nothing and count the calls; the one that stands in for the MFMA
+// scoring kernels also checks the plan it is handed against what those kernels assume about it (tilings that are
+// instantiated, key chunks within the LDS capacity, chunk bookkeeping) and keeps it for the tests to look at.
 #include "../../paper_2604_06746_amd/csrc/common.h"
 
 namespace skv {
 
 static int g_launches = 0;
+static int32_t g_last_plan[8];
 extern "C" int structkv_stub_launch_count(void) { return g_launches; }
+// RB, NW, KC, planes, stream_k, RC, grid_chunks, path of the latest MFMA scoring launch
+extern "C" void structkv_stub_last_plan(int32_t* out) { for (int i = 0; i < 8; ++i) out[i] = g_last_plan[i]; }
 
-hipError_t launch_score_mfma_ring(const structkv_shape&, const ScorePlan&, const SeqTable&, const void*, const void*,
-                                  int64_t, int64_t, float, float*, const float*, float*, int64_t, float*, int,
-                                  hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, const SeqTable& seq, const void*,
+                                  const void*, int64_t, int64_t, float, float*, const float*, float*, int64_t total,
+                                  float* probs, int pass, hipStream_t) {
+  ++g_launches;
+  const int32_t plan[8] = {p.RB, p.NW, p.KC, p.planes, p.stream_k, p.RC, (int32_t)p.grid_chunks, p.path};
+  for (int i = 0; i < 8; ++i) g_last_plan[i] = plan[i];
+  if (p.grid_chunks == 0) return hipSuccess;
+  bool ok = p.path == 0 && (s.head_dim == 64 || s.head_dim == 128) && (pass == 1 || pass == 2);
+  ok = ok && ((p.RB == 2 && p.NW == 4) || (p.RB == 1 && p.NW == 4) || (p.RB == 2 && p.NW == 1) || (p.RB == 1 && p.NW == 1));
+  ok = ok && p.RPC == 32 * p.RB && p.R == (s.n_q_heads / s.n_kv_heads) * s.window && p.RC == (p.R + p.RPC - 1) / p.RPC;
+  ok = ok && (p.NW == 4 || p.RC == 1);                          // one-wave workgroups hold a KV group's only row-chunk
+  const int planes = pass == 2 && probs == nullptr ? p.planes : 0;
+  ok = ok && (planes == 0 || planes == 1 || (planes == 2 && p.RB == 2));
+  const int cap = planes ? (p.NW == 4 ? 1280 : 1024) / planes : (p.NW == 4 ? 2048 : 896);   // keys whose sums fit the LDS
+  ok = ok && p.KC >= 32 && p.KC % 32 == 0 && (pass == 1 || p.KC <= cap);
+  ok = ok && (int64_t)s.n_kv_heads * ((p.RC + p.NW - 1) / p.NW) * p.grid_chunks < ((int64_t)1 << 31);
+  ok = ok && seq.batch >= 1 && seq.batch <= kMaxBatch && seq.chunk_start[0] == 0 && seq.chunk_start[seq.batch] == p.grid_chunks;
+  for (int b = 0; ok && b < seq.batch; ++b) {
+    const int64_t n = seq.cu[b + 1] - seq.cu[b];
+    ok = n >= 0 && seq.chunk_start[b + 1] - seq.chunk_start[b] == (n + p.KC - 1) / p.KC && seq.cu[b + 1] <= total;
+  }
+  return ok ? hipSuccess : hipErrorInvalidValue;
+}
 hipError_t launch_score_simt(const structkv_shape&, const ScorePlan&, const SeqTable&, const void*, const void*,
                              int64_t, int64_t, float, float*, const float*, float*, int64_t, float*, int,
                              hipStream_t) { ++g_launches; return hipSuccess; }

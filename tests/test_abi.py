@@ -302,3 +302,47 @@ def test_host_planning_with_stub_launchers(B):
         assert lib.structkv_score_layer_pivot(ctypes.byref(shape), fake, fake, 5000 * d, d, 2, cu1, 0.1, fake, fake, None,
                                               fake, fake, fake2, pneed, None) == B.STRUCTKV_OK, B.structkv_last_error()
     assert lib.structkv_stub_launch_count() > before
+
+
+def test_tilings_chosen_for_the_named_configurations(B):
+    """The plan the host makes for the benchmark configurations: which tiling, how many keys per workgroup, which
+    cache policy.  Stub build only (the stub of the MFMA scoring launcher keeps the plan it was handed, after
+    checking it against what the kernels assume)."""
+    lib = B._lib
+    if not hasattr(lib, "structkv_stub_last_plan"):
+        pytest.skip("the real library launches kernels; this runs against the stub build only")
+    i64 = ctypes.c_int64
+    fake, fake2 = ctypes.c_void_p(1 << 20), ctypes.c_void_p(1 << 21)
+
+    def plan(Hq, G, d, w, lens):
+        shape = B.make_shape(Hq, G, d, w, 1, False)
+        cu = (i64 * (len(lens) + 1))(*np.concatenate([[0], np.cumsum(lens)]).tolist())
+        total = int(sum(lens))
+        need = B.structkv_workspace_bytes(shape, len(lens), total)
+        assert lib.structkv_score_layer(ctypes.byref(shape), fake, fake, total * d, d, len(lens), cu, fake, fake, None,
+                                        fake2, need, None) == B.STRUCTKV_OK, B.structkv_last_error()
+        out = (ctypes.c_int32 * 8)()
+        lib.structkv_stub_last_plan(out)
+        return dict(zip(("RB", "NW", "KC", "planes", "stream_k", "RC", "grid_chunks", "path"), list(out)))
+
+    # 128K tokens, window 64: 256 rows per KV head = four waves of 64 rows; one round of 768 workgroups; K = 256 MiB streams
+    p = plan(32, 8, 128, 64, [131072])
+    assert (p["RB"], p["NW"], p["RC"], p["KC"], p["stream_k"], p["path"]) == (2, 4, 4, 1376, 1, 0)
+    assert p["grid_chunks"] == 96
+    # 32K tokens, window 32: 128 rows = four waves of 32 rows, 512 keys each (half of the resident slots); cached fetches
+    p = plan(32, 8, 128, 32, [32768])
+    assert (p["RB"], p["NW"], p["RC"], p["KC"], p["stream_k"]) == (1, 4, 4, 512, 0)
+    # the paper's window of 8: 32 rows, single-wave workgroups
+    p = plan(32, 8, 128, 8, [32768])
+    assert (p["RB"], p["NW"], p["RC"], p["KC"]) == (1, 1, 1, 256)
+    # 64 rows: one wave with two row blocks; 1M tokens: several rounds, key chunks within the LDS capacity
+    p = plan(16, 8, 128, 32, [4096])
+    assert (p["RB"], p["NW"], p["RC"]) == (2, 1, 1)
+    p = plan(32, 8, 128, 64, [1048576])
+    assert (p["RB"], p["NW"], p["stream_k"]) == (2, 4, 1) and p["KC"] <= 2048 and 5 * 96 < p["grid_chunks"] <= 6 * 96
+    # a ragged batch: chunks never straddle sequences
+    lens = [70000, 0, 33, 16384, 100000]
+    p = plan(32, 8, 128, 32, lens)
+    assert p["grid_chunks"] == sum(-(-n // p["KC"]) for n in lens) and p["stream_k"] == 1     # 364 MiB of K
+    p = plan(32, 8, 128, 32, [n // 2 for n in lens])
+    assert p["grid_chunks"] == sum(-(-(n // 2) // p["KC"]) for n in lens) and p["stream_k"] == 0
