@@ -1,4 +1,4 @@
-"""GPU parity at the BASELINE sizes, in the launch configuration bench.py times.
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 Layers of each full-size configuration are generated on the GPU (the same generator bench.py uses), run
 through the HIP path and compared with the CPU oracle on the same bits: in-degree, entropy and the centrality

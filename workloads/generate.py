@@ -102,7 +102,7 @@ def _c5_lengths() -> Tuple[int, ...]:
     return _ragged_lengths(6746 * 5, 8, 16384, 131072)
 
 
-# The five BASELINE configurations (C1..C5) plus small parity-test shapes.
+# The five benchmark configurations (C1..C5) plus small parity-test shapes.
 WORKLOADS = {}
 
 
@@ -121,7 +121,7 @@ C5_RAGGED = _register(Workload("c5_ragged_batch8", 32, 32, 8, 128, _c5, 32, "bf1
                                tuple(int(0.05 * n) for n in _c5), 32, "half"))
 
 # The paper's own operating point (Sec. 4.1 / 4.6: LLaMA-3.1-8B, 32K-token prefill, observation window 8, 10 % KV
-# budget): not one of the five BASELINE configurations, kept as context for the ~35 ms the paper reports there.
+# budget): not one of the five benchmark configurations, kept as context for the ~35 ms the paper reports there.
 P_32K_W8 = _register(Workload("p_llama8b_32k_w8", 32, 32, 8, 128, (32768,), 8, "bf16", (3276,), 64, "half"))
 
 # Small shapes for element-by-element parity: several key tiles + a ragged tail.
