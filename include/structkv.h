@@ -258,7 +258,7 @@ structkv_status structkv_block_scores(const float* scores, int32_t batch, const 
  *   variance_out[b] = (1/H_q) sum_h (1/n_b) sum_j (a_h[j] - 1/n_b)^2
  * (0 for an empty sequence).  With bf16 inputs, head_dim 64 or 128 and a window of 32 or 64 the per-head in-degrees
  * come out of the scoring pass itself (its second pass keeps one column-sum plane per query head) and the call
- * costs one scoring of the layer plus four short passes over those planes (a radix select for the top-k mass);
+ * costs one scoring of the layer plus four short kernels over those planes (a radix select for the top-k mass);
  * other shapes are re-scored head by head, which costs about as much as scoring the layer twice.
  * q_win, k, strides, cu_seqlens, shape: as structkv_score_layer.  sparsity_out, variance_out: DEVICE fp32 [B].
  * workspace: structkv_pivot_workspace_bytes(shape, longest sequence) bytes, 256-byte aligned.

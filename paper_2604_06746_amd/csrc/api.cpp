@@ -279,7 +279,7 @@ extern "C" {
 
 const char* structkv_last_error(void) { return g_err; }
 
-int32_t structkv_version(void) { return 202; }
+int32_t structkv_version(void) { return 203; }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;
@@ -865,9 +865,9 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
     if (kk < 1) kk = 1;
     if (kk > n) kk = n;
     // (the planes path keeps its partial sums where the other path keeps indices: Hq x n words)
-    if (n > 0 && from_planes && 3 * (n / 1024 + 2) + 2 <= n) {
+    if (n > 0 && from_planes && 2 * ceil_div(n, 2048) + 4 <= n && n <= ((int64_t)1 << 24)) {
       // selection scratch for the Hq heads as "sequences" of one call; its histograms are cleared by the
-      // scoring call's combine kernel and their first digit is filled by the kernel that forms the heads
+      // scoring call's combine kernel and their first digit is filled by the kernel that forms the variance
       SeqTable hseq;
       memset(&hseq, 0, sizeof(hseq));
       hseq.batch = Hq;
@@ -877,11 +877,11 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
       TopkWs tws;
       unsigned blocks = 0;
       topk_plan(hseq, 0, w8 + c.off_topk_ws, &hplan, &tws, &blocks);
-      const int Pv = pivot_plane_shares(n), Pm = (int)(blocks / (unsigned)Hq);
+      const int Pv = pivot_plane_shares(n);
       float* var_part = (float*)idx;                       // the index scratch of the other path is free here
-      float* mass_part = var_part + (size_t)Hq * Pv;
-      float* tail = mass_part + (size_t)Hq * Pm * 2;
-      if ((int64_t)Pv + 2 * (int64_t)Pm + 2 > n) return fail(STRUCTKV_ERR_UNSUPPORTED, "pivot scratch too small");
+      float* part_above = var_part + (size_t)Hq * Pv;      // ... Hq x n words of it: 2 Pv + 4 per head are used
+      float* mass_part = part_above + (size_t)Hq * Pv;
+      float* tail = mass_part + (size_t)Hq * 2;
       ScoreOpts o;
       o.planes = true;
       o.zero_ptr = tws.hist;
@@ -899,8 +899,9 @@ static structkv_status pivot_impl(const structkv_shape* shape, const void* q_win
       make_plan(*shape, &one, 1, n, true, &pp, true);
       const float* planes = (const float*)(w8 + c.off_score_ws + pp.off_colsum);   // [Hq][n]: plane g*gs + hl is head h
       SKV_HIP_CHECK(launch_pivot_planes(planes, Hq, n, 1.0f / (float)w, tws.hist, var_part, hs));
-      SKV_HIP_CHECK(launch_topk_mass(planes, hplan, tws, blocks, Pm, mass_part, tail, hs));
-      SKV_HIP_CHECK(launch_pivot_finish_planes(var_part, Pv, mass_part, Pm, tail, Hq, n, 1.0f / (float)w, sparsity_out + b,
+      // (the per-head in-degrees of the other path's scratch hold the candidate lists here)
+      SKV_HIP_CHECK(launch_topk_mass(planes, Hq, n, (uint32_t)kk, tws, heads, part_above, mass_part, tail, hs));
+      SKV_HIP_CHECK(launch_pivot_finish_planes(var_part, Pv, mass_part, 1, tail, Hq, n, 1.0f / (float)w, sparsity_out + b,
                                                variance_out + b, hs));
       continue;
     }

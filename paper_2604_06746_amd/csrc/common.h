@@ -148,8 +148,8 @@ hipError_t launch_pivot_finish(const float* part, int H, int64_t n, float inv_w,
 int pivot_plane_shares(int64_t n);
 hipError_t launch_pivot_planes(const float* heads, int H, int64_t n, float inv_w, uint32_t* hist, float* part,
                                hipStream_t st);
-hipError_t launch_topk_mass(const float* scores, const SeqTable& plan, const TopkWs& ws, unsigned blocks,
-                            int part_stride, float* part, float* tail, hipStream_t st);
+hipError_t launch_topk_mass(const float* rows, int H, int64_t n, uint32_t kk, const TopkWs& ws, float* cand,
+                            float* part_above, float* mass, float* tail, hipStream_t st);
 hipError_t launch_pivot_finish_planes(const float* var_part, int Pv, const float* mass_part, int Pm, const float* tail,
                                       int H, int64_t n, float inv_w, float* sparsity, float* variance, hipStream_t st);
 hipError_t launch_block_scores(const float* scores, const SeqTable& seq, int block, float* out, hipStream_t st);

@@ -36,6 +36,13 @@ typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 constexpr float kNegBig = -1.0e30f;
 
+// x of lane l + x of lane l + 32, in both lanes (the lower half's value first): one vector instruction that swaps
+// the halves of two registers, no trip through the LDS crossbar and no wait for it inside the key loop
+__device__ __forceinline__ float add_lane_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <bool V> using BoolC = std::integral_constant<bool, V>;
 template <int V> using IntC = std::integral_constant<int, V>;
 // a ring slot is either a compile-time number (key loop unrolled over the slots) or a run-time one
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
 #pragma unroll
       for (int sp = 0; sp < NP; ++sp) {
         float cs = PPW == 2 ? csp[sp] : cs0 + cs1;
-        cs += __shfl_xor(cs, 32);
+        cs = add_lane_halves(cs);
         const uint32_t a = a0 + (uint32_t)(sp * KCAP * 4);
         const float val = live ? cs : 0.f;
         if (lh == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(val) : "memory");
@@ -405,7 +412,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     } else if (PASS == 2) {
       float cs = cs0 + cs1;
       if (NW == 1) {
-        cs += __shfl_xor(cs, 32);
+        cs = add_lane_halves(cs);
         if (lh == 0)
           asm volatile("ds_write_b32 %0, %1" : : "v"(csout_lds + (uint32_t)((jbase - key0 + l32) * 4)), "v"(cs) : "memory");
       } else {

@@ -72,9 +72,11 @@ __global__ __launch_bounds__(kThreads) void topk_init_kernel(SeqTable seq, int k
     idx_out[seq.out_off[b] + seq.k[b] + i] = (int32_t)(m + i);
 }
 
-// exclusive scan of one value per thread over the workgroup (256 threads = 4 waves); returns the total.
-// Shuffle scan inside each wave, then the four wave totals through LDS.
-__device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t* sh /*[>=4]*/, uint32_t* excl) {
+// exclusive scan of one value per thread over the workgroup (THREADS / 64 waves); returns the total.
+// Shuffle scan inside each wave, then the wave totals through LDS.
+template <int THREADS = kThreads>
+__device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t* sh /*[>= THREADS / 64]*/, uint32_t* excl) {
+  constexpr int NWV = THREADS / 64;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   uint32_t x = v;
 #pragma unroll
@@ -84,19 +86,25 @@ __device__ inline uint32_t block_excl_scan(uint32_t v, uint32_t* sh /*[>=4]*/, u
   }
   if (lane == 63) sh[wv] = x;
   __syncthreads();
-  const uint32_t w0 = sh[0], w1 = sh[1], w2 = sh[2], w3 = sh[3];
-  const uint32_t base = wv == 0 ? 0u : (wv == 1 ? w0 : (wv == 2 ? w0 + w1 : w0 + w1 + w2));
+  uint32_t base = 0u, total = 0u;
+#pragma unroll
+  for (int i = 0; i < NWV; ++i) {
+    const uint32_t wsum = sh[i];
+    if (i < wv) base += wsum;
+    total += wsum;
+  }
   *excl = base + x - v;
   __syncthreads();
-  return w0 + w1 + w2 + w3;
+  return total;
 }
 
 // Scan `nb` bins of a merged histogram from the top until `krem` keys are covered.
 // Returns the bin (all threads), and how many keys lie above it.
-__device__ inline void select_bin(const uint32_t* __restrict__ gh, int nb, uint32_t krem, uint32_t* scan,
+template <int THREADS = kThreads>
+__device__ inline void select_bin(const uint32_t* __restrict__ gh, int nb, uint32_t krem, uint32_t* scan /*[>= THREADS / 64]*/,
                                   uint32_t* res, uint32_t* bin_out, uint32_t* above_out) {
   const int t = threadIdx.x;
-  const int per = nb / kThreads;   // 8 or 4
+  const int per = nb / THREADS;   // 8 or 4 with 256 threads, 2 or 1 with 1024
   uint32_t mine[8];
   uint32_t sum = 0;
 #pragma unroll
@@ -106,7 +114,7 @@ __device__ inline void select_bin(const uint32_t* __restrict__ gh, int nb, uint3
   }
   if (t == 0) { res[0] = 0u; res[1] = 0u; }
   uint32_t excl;
-  block_excl_scan(sum, scan, &excl);
+  block_excl_scan<THREADS>(sum, scan, &excl);
   if (excl < krem && excl + sum >= krem) {
     uint32_t run = excl;
 #pragma unroll
@@ -335,40 +343,68 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
   }
 }
 
-// Sum of the k largest scores instead of their indices (the top-k mass of the pivot detector's sparsity, Eq. 5):
-// the last step of the same radix select.  Workgroup share as in the other kernels; writes the sum of its scores
-// ABOVE the k-th largest key T, in a fixed order, to part[(b*part_stride + rank of the workgroup)*2 + 1]; the
-// `need` selected scores that EQUAL T all have T's value, so the first workgroup of a sequence just records the
-// pair (need, value of T) in tail[2b], tail[2b+1] for whoever adds the partial sums up.
+// Sum of the k largest scores of each of H equally long rows instead of their indices (the top-k mass of the pivot
+// detector's sparsity, Eq. 5), after the first digit's histogram of every row has been built by whoever formed the
+// rows.  Two kernels:
+//   compact : every workgroup finds the first digit t0 of the k-th largest key from the row's histogram, adds up
+//             its scores ABOVE that digit (a partial sum per workgroup, fixed order) and appends its scores WITH that
+//             digit -- the candidates -- to the row's candidate list (one integer atomic per workgroup reserves the
+//             place; the order of the list differs from run to run, and nothing below depends on it);
+//   select  : one workgroup of 1024 threads per row takes the candidates (the first 32768 in registers), finds the two remaining
+//             digits with histograms in LDS, and adds the candidates above the k-th key T as 64-bit fixed-point
+//             integers (exact, whatever the order), `need` copies of T's own value for the ties, and the partial sums.
+// Scores must be non-negative and at most 128 (in-degrees of one head: at most the window), rows at most 2^24 long.
 __device__ inline float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
 }
 
-__global__ __launch_bounds__(kThreads) void topk_mass_kernel(const float* __restrict__ scores, SeqTable seq,
-                                                             TopkWs ws, int part_stride, float* __restrict__ part,
-                                                             float* __restrict__ tail) {
+constexpr int kSelThreads = 1024;             // the select kernel: sixteen waves per row
+constexpr int kCandPerThread = 32;            // candidates one of its threads keeps in registers (32768 in all)
+
+// a score in [0, 128) as a 64-bit fixed-point integer with 32 fraction bits (truncated): two exact steps of 16 bits
+__device__ inline unsigned long long mass_fixed(float x) {
+  const float a = x * 65536.0f;               // exact (a power of two)
+  const float hi = floorf(a);
+  const float lo = (a - hi) * 65536.0f;       // exact: the fraction of a, scaled
+  return ((unsigned long long)(uint32_t)hi << 16) + (unsigned long long)(uint32_t)lo;
+}
+
+__global__ __launch_bounds__(kThreads) void mass_compact_kernel(const float* __restrict__ rows, int64_t n, uint32_t kk,
+                                                                TopkWs ws, float* __restrict__ cand,
+                                                                float* __restrict__ part_above) {
   short_kernel_priority();
   __shared__ uint32_t scan[4];
   __shared__ uint32_t res[2];
   __shared__ float red[kThreads];
-  const Share s = my_share(scores, seq, 0);
-  const int t = threadIdx.x;
-  const uint32_t* gh = ws.hist + (size_t)s.b * 3 * kBins;
-  float v[kPerThread];
-  const bool fast = preload_strided(s, v);
-  const uint32_t prefix = ws.state[s.b * 4 + 2], krem1 = ws.state[s.b * 4 + 3];
-  uint32_t t10, above2;
-  select_bin(gh + 2 * kBins, kLowBins, krem1, scan, res, &t10, &above2);
-  const uint32_t T = (prefix << 10) | t10;
-  float sum = 0.f;
-  if (fast) {
+  __shared__ float stage[kTargetPerBlock];
+  __shared__ uint32_t cnt, gbase;
+  const int p = blockIdx.x, h = blockIdx.y, P = gridDim.x, t = threadIdx.x, lane = t & 63;
+  const float* d = rows + (int64_t)h * n;
+  const int64_t lo = (int64_t)p * kTargetPerBlock;
+  float x[kPerThread];
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i)
-      if (s.lo + t + i * kThreads < s.hi && score_key(v[i]) > T) sum += v[i];
-  } else {
-    for (int64_t j = s.lo + t; j < s.hi; j += kThreads) {
-      const float x = s.sc[j];
-      if (score_key(x) > T) sum += x;
+  for (int i = 0; i < kPerThread; ++i) {   // loads first, the histogram scan under them
+    const int64_t j = lo + t + i * kThreads;
+    x[i] = j < n ? d[j] : 0.f;
+  }
+  if (t == 0) cnt = 0u;
+  uint32_t* gh = ws.hist + (size_t)h * 3 * kBins;
+  uint32_t t0, above0;
+  select_bin(gh, kBins, kk, scan, res, &t0, &above0);   // its barriers cover cnt = 0
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kPerThread; ++i) {
+    const bool in = lo + t + i * kThreads < n;
+    const uint32_t dg = score_key(x[i]) >> 21;
+    if (in && dg > t0) sum += x[i];
+    const bool c = in && dg == t0;
+    const unsigned long long m = __ballot(c);
+    if (m) {   // one LDS atomic per wave and step reserves the wave's places
+      const int first = __ffsll((long long)m) - 1;
+      uint32_t base = 0u;
+      if (lane == first) base = atomicAdd(&cnt, (uint32_t)__popcll(m));
+      base = __shfl(base, first);
+      if (c) stage[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = x[i];
     }
   }
   red[t] = sum;
@@ -378,11 +414,79 @@ __global__ __launch_bounds__(kThreads) void topk_mass_kernel(const float* __rest
     __syncthreads();
   }
   if (t == 0) {
-    part[((int64_t)s.b * part_stride + s.blk) * 2 + 1] = red[0];
-    if (s.blk == 0) {
-      tail[2 * s.b] = (float)(krem1 - above2);
-      tail[2 * s.b + 1] = key_score(T);
+    part_above[(int64_t)h * P + p] = red[0];
+    gbase = cnt ? atomicAdd(&gh[kBins], cnt) : 0u;   // the row's candidate counter: first word of the (unused, zeroed) digit-1 histogram
+    if (p == 0) {
+      ws.state[h * 4 + 0] = t0;
+      ws.state[h * 4 + 1] = kk - above0;
     }
+  }
+  __syncthreads();
+  float* out = cand + (int64_t)h * n + gbase;
+  for (uint32_t i = t; i < cnt; i += kThreads) out[i] = stage[i];
+}
+
+__global__ __launch_bounds__(kSelThreads) void mass_select_kernel(const float* __restrict__ cand, int64_t n, TopkWs ws,
+                                                                  const float* __restrict__ part_above, int P,
+                                                                  float* __restrict__ mass, float* __restrict__ tail) {
+  short_kernel_priority();
+  constexpr int NT = kSelThreads;
+  __shared__ uint32_t hh[kBins];
+  __shared__ uint32_t scan[NT / 64];
+  __shared__ uint32_t res[2];
+  __shared__ unsigned long long red64[NT];
+  __shared__ float redf[NT];
+  const int h = blockIdx.x, t = threadIdx.x;
+  const uint32_t* gh = ws.hist + (size_t)h * 3 * kBins;
+  const uint32_t t0 = ws.state[h * 4 + 0], krem0 = ws.state[h * 4 + 1];
+  const uint32_t c0 = gh[kBins];   // candidates = keys whose first digit is t0
+  const float* c = cand + (int64_t)h * n;
+  float v[kCandPerThread];
+#pragma unroll
+  for (int r = 0; r < kCandPerThread; ++r) {
+    const uint32_t i = (uint32_t)(r * NT + t);
+    v[r] = i < c0 ? c[i] : 0.f;
+  }
+  auto each = [&](auto f) {
+#pragma unroll
+    for (int r = 0; r < kCandPerThread; ++r)
+      if ((uint32_t)(r * NT + t) < c0) f(score_key(v[r]));
+    for (uint32_t i = (uint32_t)(kCandPerThread * NT + t); i < c0; i += NT) f(score_key(c[i]));
+  };
+  for (int i = t; i < kBins; i += NT) hh[i] = 0u;
+  __syncthreads();
+  each([&](uint32_t key) { atomicAdd(&hh[(key >> 10) & (kBins - 1)], 1u); });
+  __syncthreads();
+  uint32_t t1, above1;
+  select_bin<NT>(hh, kBins, krem0, scan, res, &t1, &above1);
+  const uint32_t krem1 = krem0 - above1;
+  for (int i = t; i < kLowBins; i += NT) hh[i] = 0u;
+  __syncthreads();
+  each([&](uint32_t key) {
+    if (((key >> 10) & (kBins - 1)) == t1) atomicAdd(&hh[key & (kLowBins - 1)], 1u);
+  });
+  __syncthreads();
+  uint32_t t2, above2;
+  select_bin<NT>(hh, kLowBins, krem1, scan, res, &t2, &above2);
+  const uint32_t T = (t0 << 21) | (t1 << 10) | t2;
+  unsigned long long acc = 0ull;
+  each([&](uint32_t key) {
+    if (key > T) acc += mass_fixed(key_score(key));
+  });
+  red64[t] = acc;
+  float pa = 0.f;
+  for (int p = t; p < P; p += NT) pa += part_above[(int64_t)h * P + p];
+  redf[t] = pa;
+  __syncthreads();
+  for (int off = NT / 2; off > 0; off >>= 1) {
+    if (t < off) { red64[t] += red64[t + off]; redf[t] += redf[t + off]; }
+    __syncthreads();
+  }
+  if (t == 0) {
+    const double m = (double)red64[0] * (1.0 / 4294967296.0) + (double)(krem1 - above2) * (double)key_score(T) + (double)redf[0];
+    mass[2 * h + 1] = (float)m;
+    tail[2 * h] = 0.f;
+    tail[2 * h + 1] = 0.f;
   }
 }
 
@@ -464,14 +568,16 @@ hipError_t launch_topk_rest(const float* scores, const SeqTable& plan, int keep_
   return hipGetLastError();
 }
 
-// digits 1 and 2, then the top-k MASS per sequence (see topk_mass_kernel); the first digit's histogram is the
-// caller's business.  Every sequence must have the same number of workgroups <= part_stride (equal lengths).
-hipError_t launch_topk_mass(const float* scores, const SeqTable& plan, const TopkWs& ws, unsigned blocks,
-                            int part_stride, float* part, float* tail, hipStream_t st) {
-  if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(topk_hist1_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, 0, ws);
-  hipLaunchKernelGGL(topk_hist2_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, 0, ws);
-  hipLaunchKernelGGL(topk_mass_kernel, dim3(blocks), dim3(kThreads), 0, st, scores, plan, ws, part_stride, part, tail);
+// The sum of the kk largest scores of each of H rows of n scores (see mass_compact_kernel).  ws.hist[h][0][.] must
+// hold the histogram of the rows' first digits and ws.hist[h][1][0] must be zero; cand: H x n floats of scratch;
+// part_above: H x ceil(n / 2048) floats; the sums land in mass[2h + 1], and tail[2h], tail[2h + 1] are cleared.
+hipError_t launch_topk_mass(const float* rows, int H, int64_t n, uint32_t kk, const TopkWs& ws, float* cand,
+                            float* part_above, float* mass, float* tail, hipStream_t st) {
+  if (H == 0 || n == 0) return hipSuccess;
+  const unsigned P = (unsigned)((n + kTargetPerBlock - 1) / kTargetPerBlock);
+  hipLaunchKernelGGL(mass_compact_kernel, dim3(P, (unsigned)H), dim3(kThreads), 0, st, rows, n, kk, ws, cand, part_above);
+  hipLaunchKernelGGL(mass_select_kernel, dim3((unsigned)H), dim3(kSelThreads), 0, st, cand, n, ws, part_above, (int)P, mass,
+                     tail);
   return hipGetLastError();
 }
 

@@ -73,7 +73,7 @@ int pivot_plane_shares(int64_t n) { return (int)((n + 2047) / 2048); }
 hipError_t launch_pivot_planes(const float*, int, int64_t, float, uint32_t*, float*, hipStream_t) {
   ++g_launches; return hipSuccess;
 }
-hipError_t launch_topk_mass(const float*, const SeqTable&, const TopkWs&, unsigned, int, float*, float*, hipStream_t) {
+hipError_t launch_topk_mass(const float*, int, int64_t, uint32_t, const TopkWs&, float*, float*, float*, float*, hipStream_t) {
   ++g_launches; return hipSuccess;
 }
 hipError_t launch_pivot_finish_planes(const float*, int, const float*, int, const float*, int, int64_t, float, float*,
