@@ -91,7 +91,8 @@ void make_plan(const structkv_shape& s, const SeqTable* seq, int batch, int64_t 
     if (planes && (s.window == p->RPC || (s.window == 32 && p->RPC == 64 && gs % 2 == 0)))
       p->planes = p->RPC / s.window;
     // the kernels' LDS column-sum capacity
-    const int64_t kMaxKC = p->planes ? (p->NW == 4 ? 1280 : 1024) / p->planes : (p->NW == 4 ? 2048 : 896);
+    const int64_t kMaxKC = p->planes ? (p->NW == 4 ? (p->planes == 1 ? 1376 : 736) : 1024 / p->planes)
+                                     : (p->NW == 4 ? 2048 : 896);
     const int64_t slots = 256 * (p->NW == 4 ? 3 : 8);
     const int64_t wg_per_chunk = s.n_kv_heads * ceil_div(p->RC, p->NW);
     const int64_t chunks_per_round = slots / wg_per_chunk > 0 ? slots / wg_per_chunk : 1;
@@ -279,7 +280,7 @@ extern "C" {
 
 const char* structkv_last_error(void) { return g_err; }
 
-int32_t structkv_version(void) { return 203; }
+int32_t structkv_version(void) { return 204; }
 
 size_t structkv_workspace_bytes(const structkv_shape* shape, int32_t batch, int64_t total_tokens) {
   if (batch < 0 || batch > kMaxBatch || total_tokens < 0) return 0;

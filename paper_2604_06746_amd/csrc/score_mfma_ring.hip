@@ -71,9 +71,15 @@ template <int NW> constexpr int kKeyCap = NW == 4 ? 2048 : 896;
 
 // Pass 2 with one column-sum plane per QUERY HEAD instead of one per workgroup (the per-head in-degrees of the
 // pivot detector's metrics, Eq. 5-6): PPW planes per wave -- 1 when a wave's rows are one head's window, 2 when
-// each of its two 32-row blocks is.  Most keys a workgroup may then be given (its LDS holds NW*PPW sums per key;
-// 20 KB of them beside three 4-wave workgroups' rings, 4 KB beside eight 1-wave ones):
-template <int NW, int PPW> constexpr int kPlanesKeyCap = (NW == 4 ? 1280 : 1024) / PPW;
+// each of its two 32-row blocks is.  Most keys a workgroup may then be given: its LDS holds NW*PPW sums per key for
+// all tiles but the chunk's last THREE, whose sums go from the registers straight to global memory (no tile load is
+// requested after them any more, so these stores sit behind every load that a wait still counts) -- 20 KB of sums
+// beside three 4-wave workgroups' rings, which is what lets a 128K-token layer be ONE round of 768 workgroups with
+// 1376 keys each (21 KB already cost the third workgroup per CU).
+constexpr int kPlanesDirectTiles = 3;
+template <int NW, int PPW> constexpr int kPlanesKeyCap = NW == 4 ? (PPW == 1 ? 1376 : 736) : 1024 / PPW;
+// ... of which LDS holds
+template <int NW, int PPW> constexpr int kPlanesLdsKeys = kPlanesKeyCap<NW, PPW> - 32 * kPlanesDirectTiles;
 
 // NW = waves per workgroup (row-chunks sharing the key tiles), NBUF = tiles in the LDS ring; PPW > 0 (pass 2):
 // planes per wave as above, written to consecutive planes of `colsum`: plane g*RC*PPW + row-chunk*PPW + block.
@@ -107,7 +113,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
   // whose reads the compiler then never orders behind the tile loads in flight (with the buffers as static
   // arrays, or with their addresses taken, it loses track and waits for ALL tile loads before LDS accesses).
   constexpr bool PLANES = PPW > 0;
-  constexpr int KCAP = PASS == 2 ? (PLANES ? kPlanesKeyCap<NW, (PLANES ? PPW : 1)> : kKeyCap<NW>) : 1;
+  // (with planes: keys per plane in LDS)
+  constexpr int KCAP = PASS == 2 ? (PLANES ? kPlanesLdsKeys<NW, (PLANES ? PPW : 1)> : kKeyCap<NW>) : 1;
   static_assert(!PLANES || (PASS == 2 && !DUMP && PPW <= NRB), "per-head planes are a pass-2 output");
   // vector-ALU instructions the scheduler is asked to place after each MFMA of the next row block
   constexpr int VPM = PASS == 1 ? 8 : 4;
@@ -400,13 +407,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
       // every wave keeps its own sums, one list per head: lane halves added here, no exchange between waves
       constexpr int NP = PLANES ? PPW : 1;
       const uint32_t a0 = csout_lds + (uint32_t)((wave * NP * KCAP + (jbase - key0 + l32)) * 4);
+      const bool last = jbase + 32 * kPlanesDirectTiles >= key_end;   // the chunk's last tiles: straight to their planes
 #pragma unroll
       for (int sp = 0; sp < NP; ++sp) {
         float cs = PPW == 2 ? csp[sp] : cs0 + cs1;
         cs = add_lane_halves(cs);
         const uint32_t a = a0 + (uint32_t)(sp * KCAP * 4);
         const float val = live ? cs : 0.f;
-        if (lh == 0) asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(val) : "memory");
+        if (last) {
+          if (lh == 0 && live && jbase + l32 < key_end)
+            colsum[((int64_t)g * RC * NP + (int64_t)rc * NP + sp) * total + tok0 + jbase + l32] = val;
+        } else if (lh == 0) {
+          asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(val) : "memory");
+        }
       }
       cs0 = 0.f; cs1 = 0.f;
     } else if (PASS == 2) {
@@ -539,7 +552,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void score_mfma_ring_kern
     for (int pl = 0; pl < NW * NP; ++pl) {
       if (rc0 + pl / NP >= RC) break;
       float* out = colsum + ((int64_t)g * RC * NP + (int64_t)rc0 * NP + pl) * total + tok0 + key0;
-      for (int i = threadIdx.x; i < key_end - key0; i += 64 * NW) {
+      for (int i = threadIdx.x; i < 32 * (nsub - kPlanesDirectTiles); i += 64 * NW) {   // (the last tiles' sums are there already)
         float v;
         const uint32_t a = csout_lds + (uint32_t)(pl * KCAP + i) * 4u;
         asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a));
@@ -594,7 +607,7 @@ hipError_t launch_ring_cfg(const structkv_shape& s, const ScorePlan& p, const Se
   dim3 g((unsigned)grid), blk(64 * NW);
   // pass 2: dynamic LDS for the column sums of the key chunk and the waves' parked sums
   const int ppw = pass == 2 && probs == nullptr ? p.planes : 0;
-  const unsigned cs_bytes = ppw ? (unsigned)(NW * 1280 * 4)   // NW * PPW * kPlanesKeyCap<NW, PPW> * 4 at most
+  const unsigned cs_bytes = ppw ? (unsigned)(NW * (NW == 4 ? 1280 : 928) * 4)   // NW * PPW * kPlanesLdsKeys<NW, PPW> * 4 at most
                                 : (unsigned)(kKeyCap<NW> * 4 + (NW > 1 ? 4 * NW * 64 * 4 : 0));
   const unsigned dyn = pass == 1 ? 16u : cs_bytes;   // pass 1: the word of the rerun vote
 #define SKV_ARGS                                                                                        \

@@ -351,23 +351,16 @@ __global__ __launch_bounds__(kThreads) void topk_write_kernel(const float* __res
 //             digit -- the candidates -- to the row's candidate list (one integer atomic per workgroup reserves the
 //             place; the order of the list differs from run to run, and nothing below depends on it);
 //   select  : one workgroup of 1024 threads per row takes the candidates (the first 32768 in registers), finds the two remaining
-//             digits with histograms in LDS, and adds the candidates above the k-th key T as 64-bit fixed-point
-//             integers (exact, whatever the order), `need` copies of T's own value for the ties, and the partial sums.
-// Scores must be non-negative and at most 128 (in-degrees of one head: at most the window), rows at most 2^24 long.
+//             digits with histograms in LDS, and adds the candidates above the k-th key T as integers (they share
+//             their exponent: exact, whatever the order), `need` copies of T's own value for the ties, and the
+//             partial sums.
+// Scores must be non-negative (in-degrees), rows at most 2^24 long.
 __device__ inline float key_score(uint32_t key) {
   return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
 }
 
 constexpr int kSelThreads = 1024;             // the select kernel: sixteen waves per row
 constexpr int kCandPerThread = 32;            // candidates one of its threads keeps in registers (32768 in all)
-
-// a score in [0, 128) as a 64-bit fixed-point integer with 32 fraction bits (truncated): two exact steps of 16 bits
-__device__ inline unsigned long long mass_fixed(float x) {
-  const float a = x * 65536.0f;               // exact (a power of two)
-  const float hi = floorf(a);
-  const float lo = (a - hi) * 65536.0f;       // exact: the fraction of a, scaled
-  return ((unsigned long long)(uint32_t)hi << 16) + (unsigned long long)(uint32_t)lo;
-}
 
 __global__ __launch_bounds__(kThreads) void mass_compact_kernel(const float* __restrict__ rows, int64_t n, uint32_t kk,
                                                                 TopkWs ws, float* __restrict__ cand,
@@ -469,9 +462,13 @@ __global__ __launch_bounds__(kSelThreads) void mass_select_kernel(const float* _
   uint32_t t2, above2;
   select_bin<NT>(hh, kLowBins, krem1, scan, res, &t2, &above2);
   const uint32_t T = (t0 << 21) | (t1 << 10) | t2;
+  // every candidate carries the first digit t0 -- sign, exponent and two mantissa bits -- so the candidates share
+  // one exponent and their 24-bit significands add up exactly as integers, in any order
   unsigned long long acc = 0ull;
+  const uint32_t expo = (t0 >> 2) & 0xFFu;            // biased exponent (scores are non-negative)
+  const uint32_t hidden = expo ? 0x00800000u : 0u;    // (subnormals have no hidden one)
   each([&](uint32_t key) {
-    if (key > T) acc += mass_fixed(key_score(key));
+    if (key > T) acc += (unsigned long long)((key & 0x007FFFFFu) | hidden);
   });
   red64[t] = acc;
   float pa = 0.f;
@@ -483,7 +480,8 @@ __global__ __launch_bounds__(kSelThreads) void mass_select_kernel(const float* _
     __syncthreads();
   }
   if (t == 0) {
-    const double m = (double)red64[0] * (1.0 / 4294967296.0) + (double)(krem1 - above2) * (double)key_score(T) + (double)redf[0];
+    const double m = ldexp((double)red64[0], (int)(expo ? expo : 1u) - 150) + (double)(krem1 - above2) * (double)key_score(T) +
+                     (double)redf[0];
     mass[2 * h + 1] = (float)m;
     tail[2 * h] = 0.f;
     tail[2 * h + 1] = 0.f;

@@ -27,7 +27,7 @@ hipError_t launch_score_mfma_ring(const structkv_shape& s, const ScorePlan& p, c
   ok = ok && (p.NW == 4 || p.RC == 1);                          // one-wave workgroups hold a KV group's only row-chunk
   const int planes = pass == 2 && probs == nullptr ? p.planes : 0;
   ok = ok && (planes == 0 || planes == 1 || (planes == 2 && p.RB == 2));
-  const int cap = planes ? (p.NW == 4 ? 1280 : 1024) / planes : (p.NW == 4 ? 2048 : 896);   // keys whose sums fit the LDS
+  const int cap = planes ? (p.NW == 4 ? (planes == 1 ? 1376 : 736) : 1024 / planes) : (p.NW == 4 ? 2048 : 896);   // keys whose sums fit the LDS
   ok = ok && p.KC >= 32 && p.KC % 32 == 0 && (pass == 1 || p.KC <= cap);
   ok = ok && (int64_t)s.n_kv_heads * ((p.RC + p.NW - 1) / p.NW) * p.grid_chunks < ((int64_t)1 << 31);
   ok = ok && seq.batch >= 1 && seq.batch <= kMaxBatch && seq.chunk_start[0] == 0 && seq.chunk_start[seq.batch] == p.grid_chunks;
