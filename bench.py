@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--separate-calls", action="store_true",
                     help="chains call the four entry points one by one instead of the fused structkv_layer_step")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
+    ap.add_argument("--pivot", action="store_true",
+                    help="also time structkv_score_layer_pivot (scores + the pivot detector's sparsity and variance, "
+                         "Eq. 5-6) against structkv_score_layer, per layer, outside the timed region; single sequences")
     ap.add_argument("--cpu-sample-layers", type=int, default=-1,
                     help="layers the CPU oracle is timed on (0 = skip; default: as many, spread evenly over the "
                          "depth, as about 25 s of CPU work allow, at least 2)")
@@ -241,6 +244,29 @@ def main():
                        "frac": round(gather_bytes / (kern_us["gather_kv"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                        "algorithmic_bytes_per_launch": gather_bytes},
         }
+
+    # ---- the pivot detector's metrics from the same scoring pass (optional; not part of the timed sweep) ----
+    if args.pivot:
+        x = layers[min(3, L - 1)]
+
+        def per_call_us(f, reps=30):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                f()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+
+        sw.score_pivot(x.q_win, x.k)                      # allocates the scratch
+        for _ in range(3):                                # the clock settles over the first few hundred calls
+            per_call_us(lambda: sw.score(x.q_win, x.k), 60)
+        t_score = min(per_call_us(lambda: sw.score(x.q_win, x.k)) for _ in range(3))
+        t_pivot = min(per_call_us(lambda: sw.score_pivot(x.q_win, x.k)) for _ in range(3))
+        t_score = min(t_score, min(per_call_us(lambda: sw.score(x.q_win, x.k)) for _ in range(3)))
+        extra["pivot"] = {"score_layer_us": round(t_score, 1), "score_layer_pivot_us": round(t_pivot, 1),
+                          "ratio": round(t_pivot / t_score, 3),
+                          "note": "calls launched back to back on one stream, 30 per bracket, best of 3 brackets"}
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
