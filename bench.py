@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--separate-calls", action="store_true",
                     help="chains call the four entry points one by one instead of the fused structkv_layer_step")
     ap.add_argument("--profile-steps", type=int, default=3, help="sweeps timed kernel by kernel with events")
+    ap.add_argument("--window", type=int, default=0,
+                    help="run the workload with another observation window (the paper's default is 8): same keys, the "
+                         "queries regenerated for that window; the config line says so")
     ap.add_argument("--pivot", action="store_true",
                     help="also time structkv_score_layer_pivot (scores + the pivot detector's sparsity and variance, "
                          "Eq. 5-6) against structkv_score_layer, per layer, outside the timed region; single sequences")
@@ -71,6 +74,9 @@ def main():
     from paper_2604_06746_amd import sweep as sweep_mod
 
     wl = workloads.WORKLOADS[args.workload]
+    if args.window and args.window != wl.window:
+        import dataclasses
+        wl = dataclasses.replace(wl, name="%s_w%d" % (wl.name, args.window), window=args.window)
     torch.cuda.set_device(0)
     L = wl.n_layers
     layers = [workloads.make_layer(wl, l, "cuda") for l in range(L)]
